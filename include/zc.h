@@ -1,0 +1,210 @@
+/*
+ * zc — one rank's sharded mixed-precision optimizer step on MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only.  Every pointer is marked HOST or
+ * DEVICE below.  The caller owns every data buffer; the library owns only what
+ * a *_create call returns and the small per-device reduction workspace it
+ * allocates on first use of zc_grad_sqnorm.
+ *
+ * Stream semantics: every call that takes `hip_stream` (a hipStream_t passed
+ * as void*, NULL = the null stream) only enqueues work on it and returns; no
+ * call synchronises the device.  zc_offload_adam_step uses two extra internal
+ * copy streams that are fenced against `hip_stream` at entry and exit, so the
+ * caller sees ordinary in-order stream behaviour.
+ *
+ * Errors: every call returns a zc_status.  Argument errors are detected before
+ * anything is launched and leave all memory untouched.  zc_last_error() gives
+ * a thread-local text for the most recent failure on the calling thread.
+ *
+ * Context in the paper (arXiv 2504.09983): the passes it describes schedule
+ * all-gathers, releases and optimizer-state transfers *around* this path; the
+ * path itself is "parameter updates" on the GPU (Evaluation: Efficiency;
+ * Adaptive Offloading) over fp32 master parameters and Adam states with bf16
+ * compute copies (Experimental settings), evenly partitioned across ranks
+ * (Optimizations: Fully-sharded approach).
+ */
+#ifndef ZC_H
+#define ZC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZC_OK = 0,
+    ZC_ERR_INVALID_ARG = 1, /* NULL where required, negative size, bad hyper-parameter */
+    ZC_ERR_ALIGNMENT = 2,   /* pointer not aligned to its element type */
+    ZC_ERR_HIP = 3,         /* a HIP runtime call failed; text has the HIP error */
+    ZC_ERR_UNSUPPORTED = 4, /* valid request this build cannot serve */
+    ZC_ERR_NOMEM = 5        /* host or device allocation failed */
+} zc_status;
+
+typedef enum { ZC_F32 = 0, ZC_BF16 = 1 } zc_dtype;
+typedef enum { ZC_ADAMW = 0, ZC_ADAM_L2 = 1 } zc_mode;
+
+/*
+ * Hyper-parameters of one step.  `step` is 1-based and supplied by the caller
+ * (the library keeps no counter).  `grad_scale` multiplies every gradient
+ * before use (1.0f = none; used for loss-scale removal and clipping).
+ * Constraints: lr finite, 0 <= beta1 < 1, 0 <= beta2 < 1, eps >= 0,
+ * weight_decay finite, grad_scale finite, step >= 1, mode in zc_mode.
+ */
+typedef struct {
+    float lr;
+    float beta1;
+    float beta2;
+    float eps;
+    float weight_decay;
+    float grad_scale;
+    int64_t step;
+    int32_t mode;
+    int32_t reserved; /* must be 0 */
+} zc_adam_hparams;
+
+/* One contiguous piece of the gathered buffer and where it goes. */
+typedef struct {
+    int64_t src_offset; /* bf16 elements from the start of the gathered buffer */
+    void *dst;          /* DEVICE, 2-byte aligned, room for numel bf16 values */
+    int64_t numel;      /* bf16 elements, >= 0 */
+} zc_segment;
+
+typedef struct zc_unshard_plan zc_unshard_plan;
+typedef struct zc_offload_ctx zc_offload_ctx;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int zc_version(void);
+
+/* Text of the last failure on this thread ("" if none).  Static storage. */
+const char *zc_last_error(void);
+
+/*
+ * Fused Adam / AdamW update over a flat fp32 partition, in place (paper:
+ * "parameter updates" kept on the GPU, Evaluation: Adaptive Offloading; fp32
+ * parameters, gradients and Adam states, Experimental settings).
+ *
+ * Per element i, with t = hp->step, bc1 = 1-beta1^t, bc2 = 1-beta2^t:
+ *   g  = upcast(g[i]) * grad_scale            (ZC_ADAM_L2: g += wd * p[i])
+ *   m[i] = beta1*m[i] + (1-beta1)*g
+ *   v[i] = beta2*v[i] + (1-beta2)*g*g
+ *   p[i] = p[i]*(1 - lr*wd) [ZC_ADAMW only] - (lr/bc1) * m[i] / (sqrt(v[i]/bc2) + eps)
+ *   bf16_out[i] = round-to-nearest-even bf16 of the stored p[i]   (if not NULL)
+ *
+ * p, m, v      DEVICE fp32[n], 4-byte aligned, updated in place.
+ * g            DEVICE, fp32[n] (ZC_F32, 4-byte aligned) or bf16[n] bit
+ *              patterns (ZC_BF16, 2-byte aligned); read only.
+ * bf16_out     DEVICE uint16[n] or NULL; must not alias p, m, v, g.
+ * skip_flag    DEVICE int32 or NULL; when *skip_flag != 0 at execution time
+ *              the step leaves every buffer untouched (overflowed step).
+ * n            elements, >= 0 (0 is a no-op); any size up to 2^40.
+ * Vector (128-bit) access is used when p, m, v are 16-byte aligned and g,
+ * bf16_out are aligned to 4 elements; otherwise a scalar kernel runs.
+ * Returns ZC_ERR_INVALID_ARG / ZC_ERR_ALIGNMENT before launching anything.
+ */
+zc_status zc_adam_step(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,
+                       int64_t n, const zc_adam_hparams *hp, uint16_t *bf16_out,
+                       const int32_t *skip_flag, void *hip_stream);
+
+/*
+ * Standalone fp32 -> bf16 copy into the all-gather send buffer (paper: bf16
+ * compute copies of fp32 masters, Experimental settings; the shards are what
+ * the all-gather sends, Fully-sharded approach).  Round-to-nearest-even; NaN
+ * stays NaN with the quiet bit set; no flush of subnormals.  Bit-identical to
+ * the bf16_out of zc_adam_step for the same fp32 input.
+ * src DEVICE fp32[n]; dst DEVICE uint16[n]; must not overlap.
+ */
+zc_status zc_cast_bf16(const float *src, uint16_t *dst, int64_t n, void *hip_stream);
+
+/*
+ * Host-only helper: flat even partition of `ntensors` tensors over `world`
+ * ranks (paper: each parameter evenly partitioned across all GPUs,
+ * Fully-sharded approach; here applied to the flattened concatenation).
+ * offsets_out[t] = sum of numels[0..t); *total_out = T = sum of all numels;
+ * *shard_numel_out = ceil(ceil(T/world)/shard_align)*shard_align.  The
+ * gathered buffer has world * shard_numel elements; elements >= T are padding.
+ * All pointers HOST.  Touches no GPU.
+ */
+zc_status zc_flat_layout(const int64_t *numels, int64_t ntensors, int32_t world,
+                         int64_t shard_align, int64_t *offsets_out,
+                         int64_t *shard_numel_out, int64_t *total_out);
+
+/*
+ * Unshard: copy pieces of the gathered flat bf16 buffer (what the all-gather
+ * produced: the large buffer B_ag of Proactive prefetching / Selective
+ * unsharding) into separately allocated per-layer tensors.  Bit copy.
+ *
+ * zc_unshard_plan_create validates the HOST segment table (offsets and sizes
+ * inside [0, gathered_numel], non-NULL 2-byte-aligned dst for non-empty
+ * segments), and uploads a descriptor table to the current device.
+ * Destination ranges must not overlap each other or the gathered buffer (not
+ * checked).  The plan stays valid until destroyed; dst pointers are captured.
+ * zc_unshard enqueues one kernel; `gathered` is DEVICE uint16[gathered_numel],
+ * 2-byte aligned.  An empty plan (nsegs == 0 or all numel == 0) is a no-op.
+ */
+zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs,
+                                 int64_t gathered_numel, zc_unshard_plan **out);
+zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void *hip_stream);
+zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
+
+/*
+ * Offloaded step (paper: Adaptive offloading moves optimizer-state fragments
+ * to host memory and overlaps the copies with computation while the update
+ * itself stays on the GPU).  Elements [0, n_resident) of the partition live
+ * in DEVICE arrays p_dev/m_dev/v_dev; elements [n_resident, n_resident +
+ * n_streamed) live in pinned HOST arrays p_host/m_host/v_host and are streamed
+ * host -> staging slot -> kernel -> host in chunks of chunk_bytes per array,
+ * with num_buffers staging slots, copies and kernel on separate streams.
+ * Results are bit-identical to zc_adam_step over the concatenation.
+ *
+ * zc_offload_create   chunk_bytes: bytes per fp32 array per chunk, a positive
+ *                     multiple of 4096 (64 MiB in the reference workload);
+ *                     num_buffers in [1, 8].  Allocates 3*num_buffers*
+ *                     chunk_bytes of device staging memory, two streams, events.
+ * zc_offload_adam_step
+ *   p_dev,m_dev,v_dev DEVICE fp32[n_resident] (may be NULL when n_resident==0)
+ *   p_host,...        HOST fp32[n_streamed], allocated with hipHostMalloc (or
+ *                     torch pin_memory); checked, unpinned -> INVALID_ARG.
+ *   g_dev             DEVICE, n_resident + n_streamed elements of g_dtype.
+ *   bf16_out_dev      DEVICE uint16[n_resident + n_streamed] or NULL.
+ *   A context serves one step at a time; concurrent calls on one context race.
+ */
+zc_status zc_offload_create(int64_t chunk_bytes, int32_t num_buffers, zc_offload_ctx **out);
+zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, float *v_dev,
+                               int64_t n_resident, float *p_host, float *m_host,
+                               float *v_host, int64_t n_streamed, const void *g_dev,
+                               zc_dtype g_dtype, const zc_adam_hparams *hp,
+                               uint16_t *bf16_out_dev, const int32_t *skip_flag,
+                               void *hip_stream);
+zc_status zc_offload_destroy(zc_offload_ctx *ctx);
+
+/*
+ * Squared L2 norm of the gradient partition and a non-finite flag (the
+ * overflow check and clipping input that precede a mixed-precision step; not
+ * in the paper, which only states that fp32 gradients are kept).
+ * g DEVICE fp32[n] or bf16[n]; sqnorm_out DEVICE float; found_inf_out DEVICE
+ * int32, set to 1 when any element is NaN/Inf else 0.  Deterministic for a
+ * given n (fixed reduction tree).  n == 0 writes 0 and 0.
+ */
+zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
+                         int32_t *found_inf_out, void *hip_stream);
+
+/*
+ * Tuning knobs for measurement sweeps (process-wide, not thread-safe against
+ * concurrent launches).  Unknown key -> ZC_ERR_INVALID_ARG.  Keys:
+ *   "adam.rows"        rows of 4 elements per lane per tile: 1, 2 or 4
+ *   "adam.blocks_per_cu" 0 = one tile per workgroup, k>0 = persistent grid of
+ *                      k workgroups per CU striding over tiles
+ *   "adam.nontemporal" 0/1 non-temporal loads and stores
+ *   "adam.arith"       0 = fp32 only, 1 = fp64 multiply-adds with fp32 sqrt/div,
+ *                      2 = fp64 throughout
+ *   "copy.blocks_per_cu", "copy.nontemporal"   same for cast and unshard
+ *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host
+ */
+zc_status zc_tune_set(const char *key, int64_t value);
+zc_status zc_tune_get(const char *key, int64_t *value_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZC_H */

@@ -1,0 +1,407 @@
+"""Pins for the CPU oracle's Adam(W) step.  None of them re-types its formula:
+they are closed forms, invariants, a 50-digit decimal brute force written from
+the textbook definition with different algebra, and a library optimizer."""
+from decimal import Decimal, getcontext
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_09983_amd import synth
+
+HP = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+def f32(x):
+    return np.asarray(x, dtype=np.float32)
+
+
+def ulp_diff(a, b):
+    """Distance in fp32 ulps (monotone integer mapping)."""
+    def key(x):
+        i = np.ascontiguousarray(x, dtype=np.float32).view(np.int32).astype(np.int64)
+        return np.where(i < 0, -(i & 0x7FFFFFFF), i)
+    return np.abs(key(a) - key(b))
+
+
+def fresh(n, seed=0):
+    rng = np.random.default_rng(seed)
+    p = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    return p, np.zeros(n, np.float32), np.zeros(n, np.float32)
+
+
+# ---- step 1 from zero state: delta p = -lr * g / (|g| + eps) ---------------
+
+def test_step1_is_lr_sign_g():
+    n = 4096
+    p, m, v = fresh(n)
+    p0 = p.copy()
+    rng = np.random.default_rng(1)
+    g = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g[np.abs(g) < 1e-5] = 1e-5
+    hp = dict(HP, weight_decay=0.0)
+    oracle.adam_step(p, m, v, g, step=1, **hp)
+    lr = float(np.float32(hp["lr"]))
+    delta = p.astype(np.float64) - p0.astype(np.float64)
+    # exact closed form, up to one rounding of p to fp32
+    eps = float(np.float32(hp["eps"]))
+    gd = g.astype(np.float64)
+    want = -lr * gd / (np.abs(gd) + eps)
+    # (m, v are stored in fp32 first: up to ~1.2e-7 relative on the lr-sized term)
+    half_ulp = 0.5 * np.spacing(np.maximum(np.abs(p0), np.abs(p))).astype(np.float64)
+    assert np.all(np.abs(delta - want) <= half_ulp + 2e-7 * lr)
+    # and the coarse statement: lr * sign(g) within 1e-3 relative
+    assert np.all(np.abs(delta + lr * np.sign(gd)) <= 1.1e-3 * lr + np.spacing(np.abs(p0)))
+    # first moments after one step
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))
+    assert np.array_equal(m, ((1 - b1) * gd).astype(np.float32))
+    assert np.array_equal(v, ((1 - b2) * gd * gd).astype(np.float32))
+
+
+def test_step1_sign_and_direction():
+    p = f32([1.0, 1.0, -1.0, -1.0])
+    m = np.zeros(4, np.float32)
+    v = np.zeros(4, np.float32)
+    g = f32([0.5, -0.5, 0.5, -0.5])
+    oracle.adam_step(p, m, v, g, step=1, **dict(HP, weight_decay=0.0, lr=1e-2))
+    # parameters move against the gradient by ~lr
+    assert np.allclose(p, [0.99, 1.01, -1.01, -0.99], rtol=0, atol=1e-6)
+    assert np.all(m * g > 0) and np.all(v > 0)
+
+
+# ---- zero gradient: pure decoupled decay -----------------------------------
+
+def test_zero_grad_pure_decay_adamw():
+    n = 1000
+    p, m, v = fresh(n, 3)
+    p0 = p.astype(np.float64)
+    g = np.zeros(n, np.float32)
+    ref = p.copy()
+    lr, wd = float(np.float32(HP["lr"])), float(np.float32(HP["weight_decay"]))
+    for t in range(1, 11):
+        oracle.adam_step(p, m, v, g, step=t, **HP)
+        ref = (ref.astype(np.float64) * (1.0 - lr * wd)).astype(np.float32)
+        assert np.array_equal(p, ref), t
+    assert not m.any() and not v.any()
+    assert np.allclose(p, p0 * (1 - lr * wd) ** 10, rtol=1e-6, atol=0)
+
+
+def test_zero_grad_l2_mode_is_not_pure_decay():
+    p, m, v = fresh(16, 4)
+    p[:] = np.where(np.abs(p) < 1e-3, 1e-3, p)
+    p0 = p.copy()
+    g = np.zeros(16, np.float32)
+    oracle.adam_step(p, m, v, g, step=1, mode=oracle.ADAM_L2, **HP)
+    # the decay enters through the gradient: step 1 moves p by ~lr against sign(p)
+    lr = 1e-4
+    assert np.allclose(p - p0, -lr * np.sign(p0), rtol=2e-3, atol=0)
+    assert m.any() and v.any()
+
+
+def test_wd_zero_modes_agree():
+    n = 257
+    p1, m1, v1 = fresh(n, 5)
+    p2, m2, v2 = p1.copy(), m1.copy(), v1.copy()
+    hp = dict(HP, weight_decay=0.0)
+    for t in range(1, 4):
+        g = synth.host_grads_f32(n, t)
+        oracle.adam_step(p1, m1, v1, g, step=t, mode=oracle.ADAMW, **hp)
+        oracle.adam_step(p2, m2, v2, g, step=t, mode=oracle.ADAM_L2, **hp)
+    assert np.array_equal(p1, p2) and np.array_equal(m1, m2) and np.array_equal(v1, v2)
+
+
+# ---- constant gradient: bias correction closed form ------------------------
+
+@pytest.mark.parametrize("steps", [10, 1000])
+def test_constant_gradient_closed_form(steps):
+    gvals = f32([1e-3, -2.5e-3, 0.7, -1e-5, 3e-2, -1.0, 1e-4, 5.0])
+    n = gvals.size
+    p = f32(np.linspace(-1, 1, n))
+    p0 = p.astype(np.float64)
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    hp = dict(HP, weight_decay=0.0)
+    lr, eps = float(np.float32(hp["lr"])), float(np.float32(hp["eps"]))
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))
+    gd = gvals.astype(np.float64)
+    for t in range(1, steps + 1):
+        oracle.adam_step(p, m, v, gvals, step=t, **hp)
+        if t in (1, 2, 5, 10, steps):
+            # m_t = g (1 - b1^t), v_t = g^2 (1 - b2^t)  (fp32 state -> small rel error)
+            assert np.allclose(m, gd * (1 - b1 ** t), rtol=2e-6, atol=0), t
+            assert np.allclose(v, gd * gd * (1 - b2 ** t), rtol=1e-5, atol=0), t
+    # every step moved p by lr*g/(|g|+eps): bias corrections cancel exactly
+    want = p0 - steps * lr * gd / (np.abs(gd) + eps)
+    assert np.allclose(p, want, rtol=0, atol=steps * 1.5e-7 + 1e-9)
+    # a wrong step base (0-based) or missing correction would be off by >10%
+    # at t=1: check the first step in isolation too
+    p1 = f32(np.linspace(-1, 1, n))
+    m1 = np.zeros(n, np.float32)
+    v1 = np.zeros(n, np.float32)
+    oracle.adam_step(p1, m1, v1, gvals, step=1, **hp)
+    assert np.allclose(p1.astype(np.float64) - p0, -lr * gd / (np.abs(gd) + eps),
+                       rtol=0, atol=6e-8)
+
+
+def test_bias_correction_uses_step_argument():
+    # same state, different `step`: ratio of updates is fixed by bc1, bc2
+    m0, v0, g = 0.02, 3e-4, 0.01
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))
+    lr, eps = float(np.float32(1e-4)), float(np.float32(1e-8))
+    deltas = {}
+    for t in (1, 3, 50):
+        p = f32([0.5]); m = f32([m0]); v = f32([v0])
+        oracle.adam_step(p, m, v, f32([g]), step=t, **dict(HP, weight_decay=0.0))
+        deltas[t] = float(p[0]) - 0.5
+        mt, vt = float(m[0]), float(v[0])
+        want = -lr * (mt / (1 - b1 ** t)) / (np.sqrt(vt / (1 - b2 ** t)) + eps)
+        assert abs(deltas[t] - want) <= 3.1e-8  # half ulp of 0.5
+    assert abs(deltas[1]) > abs(deltas[3]) > abs(deltas[50]) * 0.5
+
+
+# ---- brute force in 50-digit decimal on tiny shards ------------------------
+
+def _decimal_step(p, m, v, g, t, lr, b1, b2, eps, wd, scale, l2):
+    """Textbook Adam, algebra deliberately different from the oracle's:
+    p <- p - lr*(wd*p [decoupled]) - lr * m_hat / (sqrt(v_hat) + eps)."""
+    getcontext().prec = 60
+    D = Decimal
+    p, m, v, g = D(float(p)), D(float(m)), D(float(v)), D(float(g)) * D(float(scale))
+    lr, b1, b2, eps, wd = (D(float(np.float32(x))) for x in (lr, b1, b2, eps, wd))
+    if l2:
+        g = g + wd * p
+    m_new = b1 * m + (1 - b1) * g
+    v_new = b2 * v + (1 - b2) * g * g
+    m32 = np.float32(float(m_new))
+    v32 = np.float32(float(v_new))
+    m_hat = D(float(m32)) / (1 - b1 ** t)
+    v_hat = D(float(v32)) / (1 - b2 ** t)
+    step = lr * m_hat / (v_hat.sqrt() + eps)
+    p_new = p - step
+    if not l2:
+        p_new -= lr * wd * p
+    return p_new, m_new, v_new, m32, v32
+
+
+CASES = [
+    # p, m, v, g
+    (0.5, 0.0, 0.0, 0.0),
+    (-0.25, 0.0, 0.0, 1e-8),
+    (0.02, 0.0, 0.0, -1e-8),
+    (1.5, 1e-3, 1e-6, 1e4),
+    (-3.0, -2e-4, 4e-8, 1e-3),
+    (1e-3, 5e-5, 1e-40, 0.0),       # subnormal v
+    (-1e-3, 0.0, 1e-45, 3e-23),     # g*g underflows towards subnormal
+    (0.017, 3.3e-4, 2.2e-7, -7.7e-4),
+]
+
+
+@pytest.mark.parametrize("l2", [False, True])
+@pytest.mark.parametrize("t", [1, 2, 7, 1000])
+def test_decimal_brute_force(t, l2):
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    p = f32([c[0] for c in CASES]); m = f32([c[1] for c in CASES])
+    v = f32([c[2] for c in CASES]); g = f32([c[3] for c in CASES])
+    p0, m0, v0 = p.copy(), m.copy(), v.copy()
+    scale = 0.5
+    oracle.adam_step(p, m, v, g, step=t, grad_scale=scale,
+                     mode=oracle.ADAM_L2 if l2 else oracle.ADAMW, **hp)
+    for i in range(len(CASES)):
+        pe, me, ve, m32, v32 = _decimal_step(p0[i], m0[i], v0[i], g[i], t, hp["lr"], hp["beta1"],
+                                             hp["beta2"], hp["eps"], hp["weight_decay"], scale, l2)
+        assert m[i] == m32 and v[i] == v32, (i, m[i], m32, v[i], v32)
+        # p within half an ulp (+ the tiniest slack for double rounding) of exact
+        err = abs(Decimal(float(p[i])) - pe)
+        half_ulp = Decimal(float(np.spacing(np.abs(p[i])))) / 2
+        assert err <= half_ulp * Decimal("1.000001"), (i, p[i], pe)
+
+
+def test_hand_computed_single_element():
+    # beta1=0.5, beta2=0.75, t=2, eps=0, wd=0, lr=0.25 (all exact in binary)
+    # m=1, v=4, g=2:  m' = 0.5+1 = 1.5 ; v' = 3+1 = 4
+    # bc1 = 1-0.25 = 0.75 -> m_hat = 2 ; bc2 = 1-0.5625 = 0.4375 -> v_hat = 64/7
+    # p' = 1 - 0.25*2/sqrt(64/7) = 1 - 0.5*sqrt(7)/8 = 0.834640543...
+    p = f32([1.0]); m = f32([1.0]); v = f32([4.0])
+    oracle.adam_step(p, m, v, f32([2.0]), lr=0.25, beta1=0.5, beta2=0.75, eps=0.0,
+                     weight_decay=0.0, step=2)
+    assert m[0] == 1.5 and v[0] == 4.0
+    assert p[0] == np.float32(1 - 0.5 * 7 ** 0.5 / 8)
+    # with decoupled decay wd=0.5: p' = 1*(1-0.125) - 0.16535946 = 0.70964054
+    p = f32([1.0]); m = f32([1.0]); v = f32([4.0])
+    oracle.adam_step(p, m, v, f32([2.0]), lr=0.25, beta1=0.5, beta2=0.75, eps=0.0,
+                     weight_decay=0.5, step=2)
+    assert p[0] == np.float32(0.875 - 0.5 * 7 ** 0.5 / 8)
+    # eps outside the square root: v_hat=0 and m_hat!=0 gives m_hat/eps
+    p = f32([0.0]); m = f32([0.5]); v = f32([0.0])
+    oracle.adam_step(p, m, v, f32([0.0]), lr=0.25, beta1=0.5, beta2=0.75, eps=0.5,
+                     weight_decay=0.0, step=1)
+    # m' = 0.25, bc1 = 0.5 -> m_hat = 0.5 ; p' = -0.25*0.5/0.5
+    assert p[0] == np.float32(-0.25)
+
+
+# ---- second opinion: a library optimizer -----------------------------------
+
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+def test_against_torch_adamw_fp64(wd):
+    torch = pytest.importorskip("torch")
+    n = 5000
+    p, m, v = fresh(n, 7)
+    hp = dict(HP, weight_decay=wd)
+    tp = torch.tensor(p.astype(np.float64), requires_grad=True)
+    opt = torch.optim.AdamW([tp], lr=float(np.float32(hp["lr"])),
+                            betas=(float(np.float32(0.9)), float(np.float32(0.999))),
+                            eps=float(np.float32(hp["eps"])),
+                            weight_decay=float(np.float32(wd)), foreach=False, fused=False)
+    for t in range(1, 11):
+        g = synth.host_grads_f32(n, t)
+        oracle.adam_step(p, m, v, g, step=t, **hp)
+        tp.grad = torch.tensor(g.astype(np.float64))
+        opt.step()
+    ref = tp.detach().numpy()
+    # library keeps fp64 state, the oracle fp32 state: agreement to fp32 accuracy
+    assert np.all(np.abs(p - ref) <= 1e-6 * np.abs(ref) + 1e-7)
+    # tighter: the oracle rounds p to fp32 once per step (10 half-ulps at most) and
+    # each step's lr-sized term carries ~1e-7 relative from the fp32 m, v
+    assert np.all(np.abs(p - ref) <= 10 * 1e-4 * 3e-7 + 5.5 * np.spacing(np.abs(p)))
+    st = opt.state[tp]
+    assert np.allclose(m, st["exp_avg"].numpy(), rtol=1e-6, atol=1e-9)
+    assert np.allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-6, atol=1e-13)
+
+
+def test_against_torch_adam_l2_fp64():
+    torch = pytest.importorskip("torch")
+    n = 3000
+    p, m, v = fresh(n, 8)
+    tp = torch.tensor(p.astype(np.float64), requires_grad=True)
+    opt = torch.optim.Adam([tp], lr=float(np.float32(1e-4)),
+                           betas=(float(np.float32(0.9)), float(np.float32(0.999))),
+                           eps=float(np.float32(1e-8)), weight_decay=float(np.float32(0.01)),
+                           foreach=False, fused=False)
+    for t in range(1, 6):
+        g = synth.host_grads_f32(n, t)
+        oracle.adam_step(p, m, v, g, step=t, mode=oracle.ADAM_L2, **HP)
+        tp.grad = torch.tensor(g.astype(np.float64))
+        opt.step()
+    ref = tp.detach().numpy()
+    assert np.all(np.abs(p - ref) <= 1e-6 * np.abs(ref) + 1e-7)
+
+
+# ---- structure: independence, bf16 grads, scale, skip, NaN ------------------
+
+def test_elementwise_independence_and_split_calls():
+    n = 1001
+    p, m, v = fresh(n, 9)
+    m[:] = synth.host_normal(n, 1e-4, 11)
+    v[:] = np.abs(synth.host_normal(n, 1e-7, 12))
+    g = synth.host_grads_f32(n, 1)
+    a = [x.copy() for x in (p, m, v)]
+    oracle.adam_step(*a, g, step=3, **HP)
+    # permutation
+    perm = np.random.default_rng(0).permutation(n)
+    b = [np.ascontiguousarray(x[perm]) for x in (p, m, v)]
+    oracle.adam_step(*b, np.ascontiguousarray(g[perm]), step=3, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x[perm], y)
+    # split into two calls
+    k = 333
+    c1 = [x[:k].copy() for x in (p, m, v)]
+    c2 = [x[k:].copy() for x in (p, m, v)]
+    oracle.adam_step(*c1, g[:k].copy(), step=3, **HP)
+    oracle.adam_step(*c2, g[k:].copy(), step=3, **HP)
+    for x, y1, y2 in zip(a, c1, c2):
+        assert np.array_equal(x, np.concatenate([y1, y2]))
+
+
+def test_bf16_grads_equal_upcast_fp32_grads():
+    n = 777
+    p, m, v = fresh(n, 10)
+    gb = oracle.cast_bf16(synth.host_grads_f32(n, 2))
+    gf = oracle.upcast_bf16(gb)
+    a = [x.copy() for x in (p, m, v)]
+    b = [x.copy() for x in (p, m, v)]
+    oracle.adam_step(*a, gb, step=1, **HP)
+    oracle.adam_step(*b, gf, step=1, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_grad_scale_is_premultiplication():
+    n = 512
+    p, m, v = fresh(n, 13)
+    g = synth.host_grads_f32(n, 3)
+    a = [x.copy() for x in (p, m, v)]
+    b = [x.copy() for x in (p, m, v)]
+    oracle.adam_step(*a, g, step=1, grad_scale=0.25, **HP)   # power of two: exact
+    oracle.adam_step(*b, (g * np.float32(0.25)), step=1, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_skip_touches_nothing_and_bf16_out_is_cast_of_p():
+    n = 300
+    p, m, v = fresh(n, 14)
+    g = synth.host_grads_f32(n, 4)
+    out = np.full(n, 0xABCD, np.uint16)
+    ref = [x.copy() for x in (p, m, v)]
+    oracle.adam_step(p, m, v, g, step=1, bf16_out=out, skip=True, **HP)
+    assert all(np.array_equal(x, y) for x, y in zip((p, m, v), ref))
+    assert np.all(out == 0xABCD)
+    oracle.adam_step(p, m, v, g, step=1, bf16_out=out, **HP)
+    assert np.array_equal(out, oracle.cast_bf16(p))
+
+
+def test_nan_gradient_poisons_only_its_element():
+    n = 9
+    p, m, v = fresh(n, 15)
+    g = synth.host_grads_f32(n, 5)
+    clean = [x.copy() for x in (p, m, v)]
+    oracle.adam_step(*clean, g, step=1, **HP)
+    g2 = g.copy()
+    g2[4] = np.nan
+    oracle.adam_step(p, m, v, g2, step=1, **HP)
+    assert np.isnan(p[4]) and np.isnan(m[4]) and np.isnan(v[4])
+    keep = np.arange(n) != 4
+    for x, y in zip((p, m, v), clean):
+        assert np.array_equal(x[keep], y[keep])
+
+
+def test_padding_stays_zero():
+    z = [np.zeros(64, np.float32) for _ in range(3)]
+    out = np.ones(64, np.uint16)
+    for t in range(1, 4):
+        oracle.adam_step(*z, np.zeros(64, np.float32), step=t, bf16_out=out, **HP)
+    assert not any(x.any() for x in z) and not out.any()
+
+
+def test_offload_definition_is_concatenation():
+    n, k = 1000, 384
+    p, m, v = fresh(n, 16)
+    g = oracle.cast_bf16(synth.host_grads_f32(n, 6))
+    whole = [x.copy() for x in (p, m, v)]
+    ow = np.zeros(n, np.uint16)
+    oracle.adam_step(*whole, g, step=2, bf16_out=ow, **HP)
+    res = [x[:k].copy() for x in (p, m, v)]
+    host = [x[k:].copy() for x in (p, m, v)]
+    oo = np.zeros(n, np.uint16)
+    oracle.offload_adam_step(*res, *host, g, step=2, bf16_out=oo, **HP)
+    for w, r, h in zip(whole, res, host):
+        assert np.array_equal(w, np.concatenate([r, h]))
+    assert np.array_equal(ow, oo)
+
+
+def test_grad_sqnorm():
+    g = f32([3.0, -4.0, 0.0, 12.0])
+    s, bad = oracle.grad_sqnorm(g)
+    assert s == 169.0 and bad == 0
+    gb = oracle.cast_bf16(g)
+    assert oracle.grad_sqnorm(gb) == (169.0, 0)
+    for poison in (np.inf, -np.inf, np.nan):
+        g2 = g.copy(); g2[2] = poison
+        s, bad = oracle.grad_sqnorm(g2)
+        assert bad == 1 and not np.isfinite(s)
+    # large but finite values do not raise the flag even if squares overflow fp32
+    s, bad = oracle.grad_sqnorm(f32([3e38, 3e38]))
+    assert bad == 0 and np.isfinite(s)
+    big = synth.host_normal(100000, 1e-3, 5)
+    s, _ = oracle.grad_sqnorm(big)
+    assert abs(s - float(np.sum(big.astype(np.float64) ** 2))) <= 1e-12 * s
