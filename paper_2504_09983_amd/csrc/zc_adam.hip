@@ -1,0 +1,382 @@
+// Fused Adam / AdamW update (+ optional bf16 copy) over a flat fp32 partition.
+//
+// One streaming pass: every element's p, m, v (fp32) and g (fp32 or bf16) is
+// read once and p, m, v (+ bf16 p) written once.  Nothing is reused, nothing is
+// a contraction, so the kernel is HBM-bound and built around 128-bit accesses:
+// a wave reads one contiguous 1 KiB row per instruction (lane l owns elements
+// 4l..4l+3 of the row), a 256-thread workgroup owns ROWS rows of 1024
+// elements per tile, and all loads of a tile are issued before any arithmetic.
+//
+// The arithmetic (paper: Adam with momentum and variance buffers in fp32 next
+// to fp32 master parameters; Experimental settings, Adaptive offloading) is
+// bias-corrected Adam with epsilon outside the square root and, in ZC_ADAMW
+// mode, decoupled weight decay applied to the old parameter.
+#include <cmath>
+
+#include "zc_internal.h"
+
+namespace zc {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct AdamScalars {
+    double b1, omb1, b2, omb2, step_size, inv_sqrt_bc2, eps, decay, wd, gscale;
+    float b1f, omb1f, b2f, omb2f, step_sizef, inv_sqrt_bc2f, epsf, lrwdf, wdf, gscalef;
+    int l2;
+};
+
+static AdamScalars make_scalars(const zc_adam_hparams *hp)
+{
+    AdamScalars s;
+    const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
+    const double t = (double)hp->step;
+    const double bc1 = 1.0 - std::pow(b1, t);
+    const double bc2 = 1.0 - std::pow(b2, t);
+    s.b1 = b1;
+    s.omb1 = 1.0 - b1;
+    s.b2 = b2;
+    s.omb2 = 1.0 - b2;
+    s.step_size = lr / bc1;
+    s.inv_sqrt_bc2 = 1.0 / std::sqrt(bc2);
+    s.eps = hp->eps;
+    s.decay = 1.0 - lr * wd;
+    s.wd = wd;
+    s.gscale = hp->grad_scale;
+    s.b1f = (float)s.b1;
+    s.omb1f = (float)s.omb1;
+    s.b2f = (float)s.b2;
+    s.omb2f = (float)s.omb2;
+    s.step_sizef = (float)s.step_size;
+    s.inv_sqrt_bc2f = (float)s.inv_sqrt_bc2;
+    s.epsf = (float)s.eps;
+    s.lrwdf = (float)(lr * wd);
+    s.wdf = (float)wd;
+    s.gscalef = (float)s.gscale;
+    s.l2 = hp->mode == ZC_ADAM_L2;
+    return s;
+}
+
+// ARITH 0: fp32 throughout (fused multiply-adds, correctly rounded sqrt / div).
+// ARITH 1: multiply-adds in fp64 (full rate on gfx950), sqrt and divide in fp32.
+// ARITH 2: fp64 throughout.
+template <int ARITH>
+__device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g, const AdamScalars &s)
+{
+    if constexpr (ARITH == 0) {
+        float gf = g * s.gscalef;
+        if (s.l2)
+            gf = fmaf(s.wdf, p, gf);
+        const float mn = fmaf(s.omb1f, gf, s.b1f * m);
+        const float vn = fmaf(s.omb2f * gf, gf, s.b2f * v);
+        const float denom = fmaf(sqrtf(vn), s.inv_sqrt_bc2f, s.epsf);
+        const float upd = mn / denom;
+        // p*(1 - lr*wd) evaluated as p - (lr*wd)*p: the tiny factor keeps its
+        // relative accuracy, which (1 - lr*wd) rounded to fp32 would not.
+        const float pd = s.l2 ? p : fmaf(-s.lrwdf, p, p);
+        p = fmaf(-s.step_sizef, upd, pd);
+        m = mn;
+        v = vn;
+    } else {
+        double gd = (double)g * s.gscale;
+        if (s.l2)
+            gd = fma(s.wd, (double)p, gd);
+        const float mn = (float)fma(s.omb1, gd, s.b1 * (double)m);
+        const float vn = (float)fma(s.omb2 * gd, gd, s.b2 * (double)v);
+        const double pd = s.l2 ? (double)p : (double)p * s.decay;
+        if constexpr (ARITH == 1) {
+            const float denom = fmaf(sqrtf(vn), s.inv_sqrt_bc2f, s.epsf);
+            const float upd = mn / denom;
+            p = (float)fma(-s.step_size, (double)upd, pd);
+        } else {
+            const double denom = fma(sqrt((double)vn), s.inv_sqrt_bc2, s.eps);
+            p = (float)(pd - s.step_size * (double)mn / denom);
+        }
+        m = mn;
+        v = vn;
+    }
+}
+
+// fp32 -> bf16 bits, round-to-nearest-even, NaN kept quiet, no flush.
+__device__ __forceinline__ uint32_t bf16_rne(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const uint32_t quiet = (u >> 16) | 0x40u;
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? quiet : rounded;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T *ptr)
+{
+    if constexpr (NT)
+        return __builtin_nontemporal_load(ptr);
+    else
+        return *ptr;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T *ptr, T val)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(val, ptr);
+    else
+        *ptr = val;
+}
+
+template <int ROWS, bool G_BF16, bool NT, int ARITH, bool GUARD>
+__device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restrict__ m4,
+                                          f32x4 *__restrict__ v4, const void *__restrict__ g,
+                                          u32x2 *__restrict__ out2, int64_t first, int64_t nvec,
+                                          const AdamScalars &s)
+{
+    f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int64_t i = first + (int64_t)r * 256;
+        if (!GUARD || i < nvec) {
+            pv[r] = ld<NT>(p4 + i);
+            mv[r] = ld<NT>(m4 + i);
+            vv[r] = ld<NT>(v4 + i);
+            if constexpr (G_BF16) {
+                const u32x2 w = ld<NT>(reinterpret_cast<const u32x2 *>(g) + i);
+                gv[r].x = __uint_as_float(w.x << 16);
+                gv[r].y = __uint_as_float(w.x & 0xFFFF0000u);
+                gv[r].z = __uint_as_float(w.y << 16);
+                gv[r].w = __uint_as_float(w.y & 0xFFFF0000u);
+            } else {
+                gv[r] = ld<NT>(reinterpret_cast<const f32x4 *>(g) + i);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int64_t i = first + (int64_t)r * 256;
+        if (!GUARD || i < nvec) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float pe = pv[r][k], me = mv[r][k], ve = vv[r][k];
+                adam_elem<ARITH>(pe, me, ve, gv[r][k], s);
+                pv[r][k] = pe;
+                mv[r][k] = me;
+                vv[r][k] = ve;
+            }
+            st<NT>(p4 + i, pv[r]);
+            st<NT>(m4 + i, mv[r]);
+            st<NT>(v4 + i, vv[r]);
+            if (out2) {
+                u32x2 w;
+                w.x = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
+                w.y = bf16_rne(pv[r].z) | (bf16_rne(pv[r].w) << 16);
+                st<NT>(out2 + i, w);
+            }
+        }
+    }
+}
+
+// Requires p, m, v 16-byte aligned and g, out aligned to 4 elements.
+template <int ROWS, bool G_BF16, bool NT, int ARITH>
+__global__ __launch_bounds__(256) void adam_vec_kernel(float *__restrict__ p, float *__restrict__ m,
+                                                       float *__restrict__ v,
+                                                       const void *__restrict__ g,
+                                                       uint16_t *__restrict__ out, int64_t n,
+                                                       int64_t ntiles, AdamScalars s,
+                                                       const int32_t *__restrict__ skip)
+{
+    if (skip && *skip != 0)
+        return;
+    const int64_t nvec = n >> 2;
+    f32x4 *p4 = reinterpret_cast<f32x4 *>(p);
+    f32x4 *m4 = reinterpret_cast<f32x4 *>(m);
+    f32x4 *v4 = reinterpret_cast<f32x4 *>(v);
+    u32x2 *out2 = reinterpret_cast<u32x2 *>(out);
+    constexpr int64_t kTileVecs = 256 * ROWS;
+
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t first = tile * kTileVecs + threadIdx.x;
+        if ((tile + 1) * kTileVecs <= nvec)
+            adam_tile<ROWS, G_BF16, NT, ARITH, false>(p4, m4, v4, g, out2, first, nvec, s);
+        else
+            adam_tile<ROWS, G_BF16, NT, ARITH, true>(p4, m4, v4, g, out2, first, nvec, s);
+    }
+
+    // The last n % 4 elements, one lane each.
+    const int64_t i = (nvec << 2) + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < 4 && i < n) {
+        float pe = p[i], me = m[i], ve = v[i];
+        float ge;
+        if constexpr (G_BF16)
+            ge = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16);
+        else
+            ge = reinterpret_cast<const float *>(g)[i];
+        adam_elem<ARITH>(pe, me, ve, ge, s);
+        p[i] = pe;
+        m[i] = me;
+        v[i] = ve;
+        if (out)
+            out[i] = (uint16_t)bf16_rne(pe);
+    }
+}
+
+// Any natural alignment: one element per lane, grid-stride.
+template <bool G_BF16, int ARITH>
+__global__ __launch_bounds__(256) void adam_scalar_kernel(float *__restrict__ p, float *__restrict__ m,
+                                                          float *__restrict__ v,
+                                                          const void *__restrict__ g,
+                                                          uint16_t *__restrict__ out, int64_t n,
+                                                          AdamScalars s,
+                                                          const int32_t *__restrict__ skip)
+{
+    if (skip && *skip != 0)
+        return;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        float pe = p[i], me = m[i], ve = v[i];
+        float ge;
+        if constexpr (G_BF16)
+            ge = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16);
+        else
+            ge = reinterpret_cast<const float *>(g)[i];
+        adam_elem<ARITH>(pe, me, ve, ge, s);
+        p[i] = pe;
+        m[i] = me;
+        v[i] = ve;
+        if (out)
+            out[i] = (uint16_t)bf16_rne(pe);
+    }
+}
+
+template <int ROWS, bool G_BF16, bool NT, int ARITH>
+static void launch_vec(dim3 grid, hipStream_t stream, float *p, float *m, float *v, const void *g,
+                       uint16_t *out, int64_t n, int64_t ntiles, const AdamScalars &s,
+                       const int32_t *skip)
+{
+    hipLaunchKernelGGL((adam_vec_kernel<ROWS, G_BF16, NT, ARITH>), grid, dim3(256), 0, stream, p, m, v,
+                       g, out, n, ntiles, s, skip);
+}
+
+template <int ROWS, bool G_BF16, bool NT>
+static void pick_arith(int arith, dim3 grid, hipStream_t stream, float *p, float *m, float *v,
+                       const void *g, uint16_t *out, int64_t n, int64_t ntiles, const AdamScalars &s,
+                       const int32_t *skip)
+{
+    if (arith == 0)
+        launch_vec<ROWS, G_BF16, NT, 0>(grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    else if (arith == 1)
+        launch_vec<ROWS, G_BF16, NT, 1>(grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    else
+        launch_vec<ROWS, G_BF16, NT, 2>(grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+}
+
+template <int ROWS, bool G_BF16>
+static void pick_nt(bool nt, int arith, dim3 grid, hipStream_t stream, float *p, float *m, float *v,
+                    const void *g, uint16_t *out, int64_t n, int64_t ntiles, const AdamScalars &s,
+                    const int32_t *skip)
+{
+    if (nt)
+        pick_arith<ROWS, G_BF16, true>(arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    else
+        pick_arith<ROWS, G_BF16, false>(arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+}
+
+template <bool G_BF16>
+static void pick_rows(int rows, bool nt, int arith, dim3 grid, hipStream_t stream, float *p, float *m,
+                      float *v, const void *g, uint16_t *out, int64_t n, int64_t ntiles,
+                      const AdamScalars &s, const int32_t *skip)
+{
+    if (rows == 1)
+        pick_nt<1, G_BF16>(nt, arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    else if (rows == 2)
+        pick_nt<2, G_BF16>(nt, arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    else
+        pick_nt<4, G_BF16>(nt, arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+}
+
+zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
+                      const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
+                      hipStream_t stream)
+{
+    if (n == 0)
+        return ZC_OK;
+    const AdamScalars s = make_scalars(hp);
+    const Tune &t = tune();
+    int cus = 0;
+    ZC_TRY(num_cus(&cus));
+    const bool g_bf16 = g_dtype == ZC_BF16;
+    const uintptr_t g_align = g_bf16 ? 8 : 16;
+    const bool vec_ok = aligned_to(p, 16) && aligned_to(m, 16) && aligned_to(v, 16) &&
+                        aligned_to(g, g_align) && (!bf16_out || aligned_to(bf16_out, 8));
+    const int arith = (int)t.adam_arith;
+
+    if (vec_ok) {
+        const int rows = (int)t.adam_rows;
+        const int64_t tile_vecs = 256 * (int64_t)rows;
+        const int64_t nvec = n >> 2;
+        int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+        int64_t blocks = ntiles > 0 ? ntiles : 1;  // block 0 also owns the n % 4 tail
+        if (t.adam_blocks_per_cu > 0 && blocks > t.adam_blocks_per_cu * cus)
+            blocks = t.adam_blocks_per_cu * cus;
+        if (blocks > 0x7FFFFFFF)
+            blocks = 0x7FFFFFFF;  // the tile loop strides, so any grid covers every tile
+        const dim3 grid((unsigned)blocks);
+        if (g_bf16)
+            pick_rows<true>(rows, t.adam_nontemporal != 0, arith, grid, stream, p, m, v, g, bf16_out, n,
+                            ntiles, s, skip_flag);
+        else
+            pick_rows<false>(rows, t.adam_nontemporal != 0, arith, grid, stream, p, m, v, g, bf16_out, n,
+                             ntiles, s, skip_flag);
+    } else {
+        int64_t blocks = (n + 255) / 256;
+        const int64_t cap = (int64_t)cus * 32;
+        if (blocks > cap)
+            blocks = cap;
+        const dim3 grid((unsigned)blocks);
+#define ZC_SCALAR(GB, AR)                                                                             \
+    hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, g, bf16_out, \
+                       n, s, skip_flag)
+        if (g_bf16) {
+            if (arith == 0) ZC_SCALAR(true, 0);
+            else if (arith == 1) ZC_SCALAR(true, 1);
+            else ZC_SCALAR(true, 2);
+        } else {
+            if (arith == 0) ZC_SCALAR(false, 0);
+            else if (arith == 1) ZC_SCALAR(false, 1);
+            else ZC_SCALAR(false, 2);
+        }
+#undef ZC_SCALAR
+    }
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
+}
+
+}  // namespace zc
+
+extern "C" zc_status zc_adam_step(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,
+                                  int64_t n, const zc_adam_hparams *hp, uint16_t *bf16_out,
+                                  const int32_t *skip_flag, void *hip_stream)
+{
+    using namespace zc;
+    if (n < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n is negative (%lld)", (long long)n);
+    if (n > kMaxElements)
+        return fail(ZC_ERR_UNSUPPORTED, "n exceeds 2^40 elements");
+    ZC_TRY(check_dtype(g_dtype));
+    ZC_TRY(check_hparams(hp));
+    if (n == 0)
+        return ZC_OK;
+    if (!p || !m || !v || !g)
+        return fail(ZC_ERR_INVALID_ARG, "p, m, v and g must not be NULL when n > 0");
+    if (!aligned_to(p, 4) || !aligned_to(m, 4) || !aligned_to(v, 4))
+        return fail(ZC_ERR_ALIGNMENT, "p, m, v must be 4-byte aligned");
+    if (!aligned_to(g, g_dtype == ZC_BF16 ? 2 : 4))
+        return fail(ZC_ERR_ALIGNMENT, "g is not aligned to its element size");
+    if (bf16_out && !aligned_to(bf16_out, 2))
+        return fail(ZC_ERR_ALIGNMENT, "bf16_out must be 2-byte aligned");
+    if (skip_flag && !aligned_to(skip_flag, 4))
+        return fail(ZC_ERR_ALIGNMENT, "skip_flag must be 4-byte aligned");
+    if (p == m || p == v || m == v || (const void *)p == g || (const void *)m == g ||
+        (const void *)v == g || (void *)bf16_out == (void *)p || (void *)bf16_out == (void *)m ||
+        (void *)bf16_out == (void *)v || (const void *)bf16_out == g)
+        return fail(ZC_ERR_INVALID_ARG, "p, m, v, g, bf16_out must be distinct buffers");
+    return launch_adam(p, m, v, g, g_dtype, n, hp, bf16_out, skip_flag, (hipStream_t)hip_stream);
+}

@@ -1,0 +1,365 @@
+// Standalone fp32 -> bf16 cast and the segmented unshard copy.
+//
+// Both are pure streaming kernels (6 and 4 bytes per element, no reuse), built
+// on 128-bit accesses with a wave touching contiguous 1 KiB (fp32 / bf16 body)
+// per instruction.
+#include <new>
+#include <vector>
+
+#include "zc_internal.h"
+
+namespace zc {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ldc(const T *ptr)
+{
+    if constexpr (NT)
+        return __builtin_nontemporal_load(ptr);
+    else
+        return *ptr;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void stc(T *ptr, T val)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(val, ptr);
+    else
+        *ptr = val;
+}
+
+// Round-to-nearest-even fp32 -> bf16 bits; NaN kept (quiet bit set); no flush.
+__device__ __forceinline__ uint32_t cast_rne(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const uint32_t quiet = (u >> 16) | 0x40u;
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? quiet : rounded;
+}
+
+constexpr int kCastRows = 4;  // 4 x 1024 elements per workgroup tile
+
+// Requires src 16-byte and dst 8-byte aligned.
+template <bool NT>
+__global__ __launch_bounds__(256) void cast_vec_kernel(const float *__restrict__ src,
+                                                       uint16_t *__restrict__ dst, int64_t n,
+                                                       int64_t ntiles)
+{
+    const int64_t nvec = n >> 2;
+    const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src);
+    u32x2 *d2 = reinterpret_cast<u32x2 *>(dst);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t first = tile * (256 * kCastRows) + threadIdx.x;
+        f32x4 x[kCastRows];
+#pragma unroll
+        for (int r = 0; r < kCastRows; ++r) {
+            const int64_t i = first + r * 256;
+            if (i < nvec)
+                x[r] = ldc<NT>(s4 + i);
+        }
+#pragma unroll
+        for (int r = 0; r < kCastRows; ++r) {
+            const int64_t i = first + r * 256;
+            if (i < nvec) {
+                u32x2 w;
+                w.x = cast_rne(x[r].x) | (cast_rne(x[r].y) << 16);
+                w.y = cast_rne(x[r].z) | (cast_rne(x[r].w) << 16);
+                stc<NT>(d2 + i, w);
+            }
+        }
+    }
+    const int64_t i = (nvec << 2) + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < 4 && i < n)
+        dst[i] = (uint16_t)cast_rne(src[i]);
+}
+
+__global__ __launch_bounds__(256) void cast_scalar_kernel(const float *__restrict__ src,
+                                                          uint16_t *__restrict__ dst, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+        dst[i] = (uint16_t)cast_rne(src[i]);
+}
+
+// ---------------------------------------------------------------------------
+// Unshard.  A segment is cut into tiles of kTileVecs 16-byte vectors of its
+// destination-aligned body; the first tile of a segment also copies the (< 8
+// element) unaligned head and tail.  Workgroups find their segment by binary
+// search over the prefix sum of tiles per segment.
+// ---------------------------------------------------------------------------
+
+constexpr int64_t kTileVecs = 1024;  // 16 KiB per tile
+constexpr int kUnroll = 4;           // kTileVecs / 256 threads
+
+struct SegDesc {
+    int64_t src_offset;
+    uint16_t *dst;
+    int64_t numel;
+    int64_t first_tile;
+};
+
+__device__ __forceinline__ u32x4 load_src_vec(const uint16_t *s, unsigned align_class, bool nt)
+{
+    // align_class: 0 = 16-byte aligned, 1 = 4-byte aligned, 2 = 2-byte aligned
+    u32x4 w;
+    if (align_class == 0) {
+        const u32x4 *q = reinterpret_cast<const u32x4 *>(s);
+        w = nt ? __builtin_nontemporal_load(q) : *q;
+    } else if (align_class == 1) {
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(s);
+        w.x = q[0];
+        w.y = q[1];
+        w.z = q[2];
+        w.w = q[3];
+    } else {
+        w.x = (uint32_t)s[0] | ((uint32_t)s[1] << 16);
+        w.y = (uint32_t)s[2] | ((uint32_t)s[3] << 16);
+        w.z = (uint32_t)s[4] | ((uint32_t)s[5] << 16);
+        w.w = (uint32_t)s[6] | ((uint32_t)s[7] << 16);
+    }
+    return w;
+}
+
+template <bool NT>
+__global__ __launch_bounds__(256) void unshard_kernel(const uint16_t *__restrict__ gathered,
+                                                      const SegDesc *__restrict__ segs,
+                                                      int64_t nsegs, int64_t ntiles)
+{
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        // Largest s with segs[s].first_tile <= tile (empty segments share their
+        // successor's first_tile and are skipped by taking the last match).
+        int64_t lo = 0, hi = nsegs;
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (segs[mid].first_tile <= tile)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const SegDesc d = segs[lo];
+        const int64_t t = tile - d.first_tile;
+        const uint16_t *src = gathered + d.src_offset;
+        uint16_t *dst = d.dst;
+        const int64_t n = d.numel;
+
+        int64_t head = (int64_t)(((16u - (unsigned)(reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u) >> 1);
+        if (head > n)
+            head = n;
+        const int64_t body_vecs = (n - head) >> 3;
+        const int64_t tail = n - head - (body_vecs << 3);
+
+        if (t == 0) {
+            if ((int64_t)threadIdx.x < head)
+                dst[threadIdx.x] = src[threadIdx.x];
+            const int64_t tail_at = head + (body_vecs << 3);
+            if ((int64_t)threadIdx.x < tail)
+                dst[tail_at + threadIdx.x] = src[tail_at + threadIdx.x];
+        }
+
+        const uint16_t *sb = src + head;
+        u32x4 *db = reinterpret_cast<u32x4 *>(dst + head);
+        const uintptr_t sa = reinterpret_cast<uintptr_t>(sb);
+        const unsigned align_class = (sa & 15u) == 0 ? 0u : ((sa & 3u) == 0 ? 1u : 2u);
+
+        const int64_t first = t * kTileVecs + threadIdx.x;
+        u32x4 w[kUnroll];
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) {
+            const int64_t i = first + k * 256;
+            if (i < body_vecs)
+                w[k] = load_src_vec(sb + (i << 3), align_class, NT);
+        }
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) {
+            const int64_t i = first + k * 256;
+            if (i < body_vecs)
+                stc<NT>(db + i, w[k]);
+        }
+    }
+}
+
+}  // namespace zc
+
+struct zc_unshard_plan {
+    zc::SegDesc *segs_dev = nullptr;
+    int64_t nsegs = 0;
+    int64_t ntiles = 0;
+    int64_t gathered_numel = 0;
+    int device = 0;
+};
+
+extern "C" {
+
+zc_status zc_cast_bf16(const float *src, uint16_t *dst, int64_t n, void *hip_stream)
+{
+    using namespace zc;
+    if (n < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n is negative (%lld)", (long long)n);
+    if (n > kMaxElements)
+        return fail(ZC_ERR_UNSUPPORTED, "n exceeds 2^40 elements");
+    if (n == 0)
+        return ZC_OK;
+    if (!src || !dst)
+        return fail(ZC_ERR_INVALID_ARG, "src and dst must not be NULL when n > 0");
+    if (!aligned_to(src, 4))
+        return fail(ZC_ERR_ALIGNMENT, "src must be 4-byte aligned");
+    if (!aligned_to(dst, 2))
+        return fail(ZC_ERR_ALIGNMENT, "dst must be 2-byte aligned");
+    const uintptr_t s0 = (uintptr_t)src, d0 = (uintptr_t)dst;
+    if (s0 < d0 + 2 * (uintptr_t)n && d0 < s0 + 4 * (uintptr_t)n)
+        return fail(ZC_ERR_INVALID_ARG, "src and dst overlap");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int cus = 0;
+    ZC_TRY(num_cus(&cus));
+    const Tune &t = tune();
+    if (aligned_to(src, 16) && aligned_to(dst, 8)) {
+        const int64_t nvec = n >> 2;
+        const int64_t tile_vecs = 256 * kCastRows;
+        const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+        int64_t blocks = ntiles > 0 ? ntiles : 1;
+        if (t.copy_blocks_per_cu > 0 && blocks > t.copy_blocks_per_cu * cus)
+            blocks = t.copy_blocks_per_cu * cus;
+        if (blocks > 0x7FFFFFFF)
+            blocks = 0x7FFFFFFF;
+        if (t.copy_nontemporal)
+            hipLaunchKernelGGL(cast_vec_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, src,
+                               dst, n, ntiles);
+        else
+            hipLaunchKernelGGL(cast_vec_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src,
+                               dst, n, ntiles);
+    } else {
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > (int64_t)cus * 32)
+            blocks = (int64_t)cus * 32;
+        hipLaunchKernelGGL(cast_scalar_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, n);
+    }
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
+}
+
+zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t gathered_numel,
+                                 zc_unshard_plan **out)
+{
+    using namespace zc;
+    if (!out)
+        return fail(ZC_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (nsegs < 0 || gathered_numel < 0)
+        return fail(ZC_ERR_INVALID_ARG, "nsegs and gathered_numel must be >= 0");
+    if (nsegs > 0 && !segs)
+        return fail(ZC_ERR_INVALID_ARG, "segs is NULL");
+    if (gathered_numel > kMaxElements * 64)
+        return fail(ZC_ERR_UNSUPPORTED, "gathered buffer exceeds 2^46 elements");
+
+    std::vector<SegDesc> table;
+    try {
+        table.reserve((size_t)nsegs);
+    } catch (const std::bad_alloc &) {
+        return fail(ZC_ERR_NOMEM, "cannot allocate the host segment table");
+    }
+    int64_t ntiles = 0;
+    for (int64_t s = 0; s < nsegs; ++s) {
+        const zc_segment &g = segs[s];
+        if (g.numel < 0 || g.src_offset < 0)
+            return fail(ZC_ERR_INVALID_ARG, "segment %lld: negative offset or size", (long long)s);
+        if (g.numel > gathered_numel || g.src_offset > gathered_numel - g.numel)
+            return fail(ZC_ERR_INVALID_ARG, "segment %lld: [%lld, +%lld) leaves the gathered buffer of %lld",
+                        (long long)s, (long long)g.src_offset, (long long)g.numel,
+                        (long long)gathered_numel);
+        if (g.numel > 0 && !g.dst)
+            return fail(ZC_ERR_INVALID_ARG, "segment %lld: dst is NULL", (long long)s);
+        if (g.numel > 0 && !aligned_to(g.dst, 2))
+            return fail(ZC_ERR_ALIGNMENT, "segment %lld: dst must be 2-byte aligned", (long long)s);
+        SegDesc d;
+        d.src_offset = g.src_offset;
+        d.dst = static_cast<uint16_t *>(g.dst);
+        d.numel = g.numel;
+        d.first_tile = ntiles;
+        if (g.numel > 0) {
+            int64_t head = (int64_t)(((16u - (unsigned)((uintptr_t)g.dst & 15u)) & 15u) >> 1);
+            if (head > g.numel)
+                head = g.numel;
+            const int64_t body_vecs = (g.numel - head) >> 3;
+            const int64_t tiles = (body_vecs + kTileVecs - 1) / kTileVecs;
+            ntiles += tiles > 0 ? tiles : 1;  // head / tail need a tile even with no body
+        }
+        table.push_back(d);
+    }
+
+    zc_unshard_plan *plan = new (std::nothrow) zc_unshard_plan;
+    if (!plan)
+        return fail(ZC_ERR_NOMEM, "cannot allocate the plan");
+    plan->nsegs = nsegs;
+    plan->ntiles = ntiles;
+    plan->gathered_numel = gathered_numel;
+    hipError_t e = hipGetDevice(&plan->device);
+    if (e == hipSuccess && nsegs > 0) {
+        e = hipMalloc(reinterpret_cast<void **>(&plan->segs_dev), sizeof(SegDesc) * (size_t)nsegs);
+        if (e == hipSuccess)
+            e = hipMemcpy(plan->segs_dev, table.data(), sizeof(SegDesc) * (size_t)nsegs,
+                          hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+        if (plan->segs_dev)
+            (void)hipFree(plan->segs_dev);
+        delete plan;
+        return hip_fail(e, "uploading the unshard descriptor table");
+    }
+    *out = plan;
+    return ZC_OK;
+}
+
+zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void *hip_stream)
+{
+    using namespace zc;
+    if (!plan)
+        return fail(ZC_ERR_INVALID_ARG, "plan is NULL");
+    if (plan->ntiles == 0)
+        return ZC_OK;
+    if (!gathered)
+        return fail(ZC_ERR_INVALID_ARG, "gathered is NULL");
+    if (!aligned_to(gathered, 2))
+        return fail(ZC_ERR_ALIGNMENT, "gathered must be 2-byte aligned");
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev != plan->device)
+        return fail(ZC_ERR_INVALID_ARG, "plan was created on device %d, current device is %d",
+                    plan->device, dev);
+    int cus = 0;
+    ZC_TRY(num_cus(&cus));
+    const Tune &t = tune();
+    int64_t blocks = plan->ntiles;
+    if (t.copy_blocks_per_cu > 0 && blocks > t.copy_blocks_per_cu * cus)
+        blocks = t.copy_blocks_per_cu * cus;
+    if (blocks > 0x7FFFFFFF)
+        blocks = 0x7FFFFFFF;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (t.copy_nontemporal)
+        hipLaunchKernelGGL(unshard_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, gathered,
+                           plan->segs_dev, plan->nsegs, plan->ntiles);
+    else
+        hipLaunchKernelGGL(unshard_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, gathered,
+                           plan->segs_dev, plan->nsegs, plan->ntiles);
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
+}
+
+zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan)
+{
+    using namespace zc;
+    if (!plan)
+        return ZC_OK;
+    hipError_t e = hipSuccess;
+    if (plan->segs_dev)
+        e = hipFree(plan->segs_dev);
+    delete plan;
+    if (e != hipSuccess)
+        return hip_fail(e, "hipFree(descriptor table)");
+    return ZC_OK;
+}
+
+}  // extern "C"

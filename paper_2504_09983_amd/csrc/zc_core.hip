@@ -1,0 +1,172 @@
+// Error reporting, tuning knobs, device queries and the host-only layout helper.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "zc_internal.h"
+
+namespace zc {
+
+static thread_local char g_err[512] = "";
+
+zc_status fail(zc_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+zc_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(ZC_ERR_HIP, "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+Tune &tune()
+{
+    static Tune t;
+    return t;
+}
+
+zc_status num_cus(int *out)
+{
+    static std::mutex mu;
+    static int cached[64];
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return fail(ZC_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int cus = 0;
+        ZC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (cus <= 0)
+            return fail(ZC_ERR_HIP, "device %d reports %d compute units", dev, cus);
+        cached[dev] = cus;
+    }
+    *out = cached[dev];
+    return ZC_OK;
+}
+
+zc_status check_dtype(zc_dtype t)
+{
+    if (t != ZC_F32 && t != ZC_BF16)
+        return fail(ZC_ERR_INVALID_ARG, "g_dtype %d is neither ZC_F32 nor ZC_BF16", (int)t);
+    return ZC_OK;
+}
+
+zc_status check_hparams(const zc_adam_hparams *hp)
+{
+    if (!hp)
+        return fail(ZC_ERR_INVALID_ARG, "hp is NULL");
+    if (!std::isfinite(hp->lr))
+        return fail(ZC_ERR_INVALID_ARG, "lr must be finite");
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f))
+        return fail(ZC_ERR_INVALID_ARG, "beta1 must be in [0, 1)");
+    if (!(hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+        return fail(ZC_ERR_INVALID_ARG, "beta2 must be in [0, 1)");
+    if (!(hp->eps >= 0.0f) || !std::isfinite(hp->eps))
+        return fail(ZC_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!std::isfinite(hp->weight_decay))
+        return fail(ZC_ERR_INVALID_ARG, "weight_decay must be finite");
+    if (!std::isfinite(hp->grad_scale))
+        return fail(ZC_ERR_INVALID_ARG, "grad_scale must be finite");
+    if (hp->step < 1)
+        return fail(ZC_ERR_INVALID_ARG, "step is 1-based, got %lld", (long long)hp->step);
+    if (hp->mode != ZC_ADAMW && hp->mode != ZC_ADAM_L2)
+        return fail(ZC_ERR_INVALID_ARG, "mode %d is neither ZC_ADAMW nor ZC_ADAM_L2", (int)hp->mode);
+    if (hp->reserved != 0)
+        return fail(ZC_ERR_INVALID_ARG, "reserved field must be 0");
+    return ZC_OK;
+}
+
+struct Knob {
+    const char *key;
+    int64_t Tune::*field;
+    int64_t lo, hi;
+};
+
+static const Knob kKnobs[] = {
+    {"adam.rows", &Tune::adam_rows, 1, 4},
+    {"adam.blocks_per_cu", &Tune::adam_blocks_per_cu, 0, 64},
+    {"adam.nontemporal", &Tune::adam_nontemporal, 0, 1},
+    {"adam.arith", &Tune::adam_arith, 0, 2},
+    {"copy.blocks_per_cu", &Tune::copy_blocks_per_cu, 0, 64},
+    {"copy.nontemporal", &Tune::copy_nontemporal, 0, 1},
+    {"offload.zero_copy", &Tune::offload_zero_copy, 0, 1},
+};
+
+static const Knob *find_knob(const char *key)
+{
+    if (!key)
+        return nullptr;
+    for (const Knob &k : kKnobs)
+        if (std::strcmp(k.key, key) == 0)
+            return &k;
+    return nullptr;
+}
+
+}  // namespace zc
+
+extern "C" {
+
+int zc_version(void) { return 100; }
+
+const char *zc_last_error(void) { return zc::g_err; }
+
+zc_status zc_tune_set(const char *key, int64_t value)
+{
+    const zc::Knob *k = zc::find_knob(key);
+    if (!k)
+        return zc::fail(ZC_ERR_INVALID_ARG, "unknown tuning key '%s'", key ? key : "(null)");
+    if (value < k->lo || value > k->hi || (k->field == &zc::Tune::adam_rows && value == 3))
+        return zc::fail(ZC_ERR_INVALID_ARG, "value %lld out of range for '%s'", (long long)value, key);
+    zc::tune().*(k->field) = value;
+    return ZC_OK;
+}
+
+zc_status zc_tune_get(const char *key, int64_t *value_out)
+{
+    const zc::Knob *k = zc::find_knob(key);
+    if (!k || !value_out)
+        return zc::fail(ZC_ERR_INVALID_ARG, "unknown tuning key or NULL output");
+    *value_out = zc::tune().*(k->field);
+    return ZC_OK;
+}
+
+zc_status zc_flat_layout(const int64_t *numels, int64_t ntensors, int32_t world, int64_t shard_align,
+                         int64_t *offsets_out, int64_t *shard_numel_out, int64_t *total_out)
+{
+    if (ntensors < 0 || world < 1 || shard_align < 1)
+        return zc::fail(ZC_ERR_INVALID_ARG, "need ntensors >= 0, world >= 1, shard_align >= 1");
+    if (ntensors > 0 && (!numels || !offsets_out))
+        return zc::fail(ZC_ERR_INVALID_ARG, "numels / offsets_out is NULL");
+    if (!shard_numel_out || !total_out)
+        return zc::fail(ZC_ERR_INVALID_ARG, "shard_numel_out / total_out is NULL");
+    const int64_t limit = zc::kMaxElements * 64;
+    int64_t running = 0;
+    for (int64_t t = 0; t < ntensors; ++t) {
+        if (numels[t] < 0)
+            return zc::fail(ZC_ERR_INVALID_ARG, "numels[%lld] is negative", (long long)t);
+        if (numels[t] > limit - running)
+            return zc::fail(ZC_ERR_UNSUPPORTED, "total size exceeds 2^46 elements");
+        running += numels[t];
+    }
+    // Write outputs only after the whole table has been validated.
+    running = 0;
+    for (int64_t t = 0; t < ntensors; ++t) {
+        offsets_out[t] = running;
+        running += numels[t];
+    }
+    const int64_t per_rank = (running + world - 1) / world;
+    *shard_numel_out = (per_rank + shard_align - 1) / shard_align * shard_align;
+    *total_out = running;
+    return ZC_OK;
+}
+
+}  // extern "C"

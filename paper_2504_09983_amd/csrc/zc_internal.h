@@ -1,0 +1,57 @@
+// Internal declarations shared by the translation units of libzc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "zc.h"
+
+namespace zc {
+
+// Records a message for zc_last_error() and returns `code`.
+zc_status fail(zc_status code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+zc_status hip_fail(hipError_t e, const char *what);
+void clear_error();
+
+#define ZC_HIP(call)                                   \
+    do {                                               \
+        hipError_t zc_e_ = (call);                     \
+        if (zc_e_ != hipSuccess)                       \
+            return ::zc::hip_fail(zc_e_, #call);       \
+    } while (0)
+
+#define ZC_TRY(call)                 \
+    do {                             \
+        zc_status zc_s_ = (call);    \
+        if (zc_s_ != ZC_OK)          \
+            return zc_s_;            \
+    } while (0)
+
+struct Tune {
+    int64_t adam_rows = 2;
+    int64_t adam_blocks_per_cu = 0;
+    int64_t adam_nontemporal = 0;
+    int64_t adam_arith = 1;
+    int64_t copy_blocks_per_cu = 0;
+    int64_t copy_nontemporal = 0;
+    int64_t offload_zero_copy = 0;
+};
+Tune &tune();
+
+// Compute units of the current device (cached per device ordinal).
+zc_status num_cus(int *out);
+
+// Host-side validation shared by the resident and the offloaded step.
+zc_status check_hparams(const zc_adam_hparams *hp);
+zc_status check_dtype(zc_dtype t);
+
+// Enqueue the fused update over n elements; arguments already validated.
+zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
+                      const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
+                      hipStream_t stream);
+
+inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+constexpr int64_t kMaxElements = int64_t(1) << 40;
+
+}  // namespace zc

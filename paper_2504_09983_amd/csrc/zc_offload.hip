@@ -1,0 +1,239 @@
+// Offloaded optimizer step: fp32 p/m/v of the streamed suffix live in pinned
+// host memory and pass through a ring of device staging slots.
+//
+// Paper context (Adaptive offloading): optimizer-state fragments are copied
+// asynchronously so that transfers overlap with computation, memory is only
+// reused after the copy has completed, and the update itself runs on the GPU.
+// Here the fragments are fixed-size chunks and the three actors are three HIP
+// streams at default priority:
+//
+//   h2d stream : wait(slot free) -> 3 x hipMemcpyAsync host->slot -> record(loaded)
+//   caller's   : wait(loaded)    -> fused update kernel on slot   -> record(updated)
+//   d2h stream : wait(updated)   -> 3 x hipMemcpyAsync slot->host -> record(slot free)
+//
+// Both copy directions run concurrently on separate DMA queues, so a full-duplex
+// host link is busy both ways while the (much shorter) kernel hides in between.
+#include <new>
+
+#include "zc_internal.h"
+
+struct zc_offload_ctx {
+    int64_t chunk_bytes = 0;
+    int64_t chunk_elems = 0;
+    int num_buffers = 0;
+    int device = 0;
+    float *staging = nullptr;  // num_buffers * 3 * chunk_elems floats
+    hipStream_t h2d = nullptr, d2h = nullptr;
+    hipEvent_t entry = nullptr, done = nullptr;
+    hipEvent_t loaded[8] = {}, updated[8] = {}, freed[8] = {};
+};
+
+namespace zc {
+
+static void destroy_ctx(zc_offload_ctx *c)
+{
+    if (!c)
+        return;
+    if (c->h2d) {
+        (void)hipStreamSynchronize(c->h2d);
+        (void)hipStreamDestroy(c->h2d);
+    }
+    if (c->d2h) {
+        (void)hipStreamSynchronize(c->d2h);
+        (void)hipStreamDestroy(c->d2h);
+    }
+    for (int i = 0; i < 8; ++i) {
+        if (c->loaded[i]) (void)hipEventDestroy(c->loaded[i]);
+        if (c->updated[i]) (void)hipEventDestroy(c->updated[i]);
+        if (c->freed[i]) (void)hipEventDestroy(c->freed[i]);
+    }
+    if (c->entry) (void)hipEventDestroy(c->entry);
+    if (c->done) (void)hipEventDestroy(c->done);
+    if (c->staging) (void)hipFree(c->staging);
+    delete c;
+}
+
+// Pinned host memory is reported as hipMemoryTypeHost; pageable memory either
+// fails the query or is reported as unregistered.
+static zc_status require_pinned(const void *ptr, const char *name)
+{
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, ptr);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();  // clear the sticky error of the failed query
+        return fail(ZC_ERR_INVALID_ARG, "%s is not pinned host memory (hipHostMalloc it)", name);
+    }
+    if (attr.type != hipMemoryTypeHost)
+        return fail(ZC_ERR_INVALID_ARG, "%s is not pinned host memory (memory type %d)", name,
+                    (int)attr.type);
+    return ZC_OK;
+}
+
+}  // namespace zc
+
+extern "C" {
+
+zc_status zc_offload_create(int64_t chunk_bytes, int32_t num_buffers, zc_offload_ctx **out)
+{
+    using namespace zc;
+    if (!out)
+        return fail(ZC_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (chunk_bytes <= 0 || chunk_bytes % 4096 != 0)
+        return fail(ZC_ERR_INVALID_ARG, "chunk_bytes must be a positive multiple of 4096");
+    if (chunk_bytes > (int64_t(1) << 32))
+        return fail(ZC_ERR_UNSUPPORTED, "chunk_bytes above 4 GiB");
+    if (num_buffers < 1 || num_buffers > 8)
+        return fail(ZC_ERR_INVALID_ARG, "num_buffers must be in [1, 8]");
+    zc_offload_ctx *c = new (std::nothrow) zc_offload_ctx;
+    if (!c)
+        return fail(ZC_ERR_NOMEM, "cannot allocate the context");
+    c->chunk_bytes = chunk_bytes;
+    c->chunk_elems = chunk_bytes / 4;
+    c->num_buffers = num_buffers;
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void **>(&c->staging), (size_t)chunk_bytes * 3 * num_buffers);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->entry, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->done, hipEventDisableTiming);
+    for (int i = 0; i < num_buffers && e == hipSuccess; ++i) {
+        e = hipEventCreateWithFlags(&c->loaded[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->updated[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->freed[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        const zc_status st = (e == hipErrorOutOfMemory)
+                                 ? fail(ZC_ERR_NOMEM, "staging ring of %lld bytes does not fit",
+                                        (long long)chunk_bytes * 3 * num_buffers)
+                                 : hip_fail(e, "creating the offload context");
+        destroy_ctx(c);
+        return st;
+    }
+    *out = c;
+    return ZC_OK;
+}
+
+zc_status zc_offload_destroy(zc_offload_ctx *ctx)
+{
+    zc::destroy_ctx(ctx);
+    return ZC_OK;
+}
+
+zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, float *v_dev,
+                               int64_t n_resident, float *p_host, float *m_host, float *v_host,
+                               int64_t n_streamed, const void *g_dev, zc_dtype g_dtype,
+                               const zc_adam_hparams *hp, uint16_t *bf16_out_dev,
+                               const int32_t *skip_flag, void *hip_stream)
+{
+    using namespace zc;
+    if (!ctx)
+        return fail(ZC_ERR_INVALID_ARG, "ctx is NULL");
+    if (n_resident < 0 || n_streamed < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n_resident and n_streamed must be >= 0");
+    if (n_resident > kMaxElements || n_streamed > kMaxElements)
+        return fail(ZC_ERR_UNSUPPORTED, "partition exceeds 2^40 elements");
+    ZC_TRY(check_dtype(g_dtype));
+    ZC_TRY(check_hparams(hp));
+    const int64_t n = n_resident + n_streamed;
+    if (n == 0)
+        return ZC_OK;
+    if (!g_dev)
+        return fail(ZC_ERR_INVALID_ARG, "g_dev is NULL");
+    const int64_t g_size = g_dtype == ZC_BF16 ? 2 : 4;
+    if (!aligned_to(g_dev, (uintptr_t)g_size))
+        return fail(ZC_ERR_ALIGNMENT, "g_dev is not aligned to its element size");
+    if (bf16_out_dev && !aligned_to(bf16_out_dev, 2))
+        return fail(ZC_ERR_ALIGNMENT, "bf16_out_dev must be 2-byte aligned");
+    if (skip_flag && !aligned_to(skip_flag, 4))
+        return fail(ZC_ERR_ALIGNMENT, "skip_flag must be 4-byte aligned");
+    if (n_resident > 0) {
+        if (!p_dev || !m_dev || !v_dev)
+            return fail(ZC_ERR_INVALID_ARG, "resident p/m/v must not be NULL when n_resident > 0");
+        if (!aligned_to(p_dev, 4) || !aligned_to(m_dev, 4) || !aligned_to(v_dev, 4))
+            return fail(ZC_ERR_ALIGNMENT, "resident p/m/v must be 4-byte aligned");
+    }
+    if (n_streamed > 0) {
+        if (!p_host || !m_host || !v_host)
+            return fail(ZC_ERR_INVALID_ARG, "host p/m/v must not be NULL when n_streamed > 0");
+        if (!aligned_to(p_host, 4) || !aligned_to(m_host, 4) || !aligned_to(v_host, 4))
+            return fail(ZC_ERR_ALIGNMENT, "host p/m/v must be 4-byte aligned");
+        if (p_host == m_host || p_host == v_host || m_host == v_host)
+            return fail(ZC_ERR_INVALID_ARG, "host p, m, v must be distinct buffers");
+    }
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev != ctx->device)
+        return fail(ZC_ERR_INVALID_ARG, "context was created on device %d, current device is %d",
+                    ctx->device, dev);
+    if (n_streamed > 0) {
+        ZC_TRY(require_pinned(p_host, "p_host"));
+        ZC_TRY(require_pinned(m_host, "m_host"));
+        ZC_TRY(require_pinned(v_host, "v_host"));
+    }
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    // Resident prefix: one ordinary launch on the caller's stream.
+    if (n_resident > 0)
+        ZC_TRY(launch_adam(p_dev, m_dev, v_dev, g_dev, g_dtype, n_resident, hp, bf16_out_dev, skip_flag,
+                           stream));
+    if (n_streamed == 0)
+        return ZC_OK;
+
+    const char *g_tail = static_cast<const char *>(g_dev) + n_resident * g_size;
+    uint16_t *out_tail = bf16_out_dev ? bf16_out_dev + n_resident : nullptr;
+
+    if (tune().offload_zero_copy) {
+        // The kernel reads and writes the pinned host arrays through the link.
+        float *pd = nullptr, *md = nullptr, *vd = nullptr;
+        ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&pd), p_host, 0));
+        ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&md), m_host, 0));
+        ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&vd), v_host, 0));
+        return launch_adam(pd, md, vd, g_tail, g_dtype, n_streamed, hp, out_tail, skip_flag, stream);
+    }
+
+    // Fence the copy streams behind whatever the caller has already enqueued.
+    ZC_HIP(hipEventRecord(ctx->entry, stream));
+    ZC_HIP(hipStreamWaitEvent(ctx->h2d, ctx->entry, 0));
+    ZC_HIP(hipStreamWaitEvent(ctx->d2h, ctx->entry, 0));
+
+    const int64_t ce = ctx->chunk_elems;
+    const int nb = ctx->num_buffers;
+    const int64_t nchunks = (n_streamed + ce - 1) / ce;
+    for (int64_t k = 0; k < nchunks; ++k) {
+        const int slot = (int)(k % nb);
+        const int64_t off = k * ce;
+        const int64_t cnt = (n_streamed - off) < ce ? (n_streamed - off) : ce;
+        const size_t bytes = (size_t)cnt * 4;
+        float *sp = ctx->staging + (int64_t)slot * 3 * ce;
+        float *sm = sp + ce;
+        float *sv = sm + ce;
+
+        if (k >= nb)
+            ZC_HIP(hipStreamWaitEvent(ctx->h2d, ctx->freed[slot], 0));
+        ZC_HIP(hipMemcpyAsync(sp, p_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
+        ZC_HIP(hipMemcpyAsync(sm, m_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
+        ZC_HIP(hipMemcpyAsync(sv, v_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
+        ZC_HIP(hipEventRecord(ctx->loaded[slot], ctx->h2d));
+
+        ZC_HIP(hipStreamWaitEvent(stream, ctx->loaded[slot], 0));
+        ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp,
+                           out_tail ? out_tail + off : nullptr, skip_flag, stream));
+        ZC_HIP(hipEventRecord(ctx->updated[slot], stream));
+
+        ZC_HIP(hipStreamWaitEvent(ctx->d2h, ctx->updated[slot], 0));
+        ZC_HIP(hipMemcpyAsync(p_host + off, sp, bytes, hipMemcpyDeviceToHost, ctx->d2h));
+        ZC_HIP(hipMemcpyAsync(m_host + off, sm, bytes, hipMemcpyDeviceToHost, ctx->d2h));
+        ZC_HIP(hipMemcpyAsync(v_host + off, sv, bytes, hipMemcpyDeviceToHost, ctx->d2h));
+        ZC_HIP(hipEventRecord(ctx->freed[slot], ctx->d2h));
+    }
+
+    // The caller's stream resumes only after the last copy-back has landed.
+    ZC_HIP(hipEventRecord(ctx->done, ctx->d2h));
+    ZC_HIP(hipStreamWaitEvent(stream, ctx->done, 0));
+    return ZC_OK;
+}
+
+}  // extern "C"

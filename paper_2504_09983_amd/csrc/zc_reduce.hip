@@ -1,0 +1,251 @@
+// Squared gradient norm and non-finite check over a flat partition.
+//
+// Streaming read (2 or 4 bytes per element).  Each lane keeps four fp32
+// partial sums (one per vector slot), a wave folds them with cross-lane
+// shuffles (DPP / permute on gfx950), waves meet in LDS, every workgroup writes
+// one double partial, and a single small workgroup folds the partials in a
+// fixed order, so the result is deterministic for a given n.
+#include <mutex>
+
+#include "zc_internal.h"
+
+namespace zc {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxPartials = 4096;
+
+struct Partial {
+    double sum;
+    uint32_t bad;
+    uint32_t pad;
+};
+
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_or(uint32_t x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        x |= (uint32_t)__shfl_xor((int)x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ void block_fold(double sum, uint32_t bad, Partial *out)
+{
+    __shared__ double s_sum[4];
+    __shared__ uint32_t s_bad[4];
+    sum = wave_sum(sum);
+    bad = wave_or(bad);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        s_sum[wave] = sum;
+        s_bad[wave] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Partial r;
+        r.sum = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+        r.bad = s_bad[0] | s_bad[1] | s_bad[2] | s_bad[3];
+        r.pad = 0;
+        *out = r;
+    }
+}
+
+// bf16 input, 8 elements (16 bytes) per lane per row.  Requires 16-byte alignment.
+__global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__restrict__ g, int64_t n,
+                                                          Partial *__restrict__ partials)
+{
+    const int64_t nvec = n >> 3;
+    const u32x4 *g4 = reinterpret_cast<const u32x4 *>(g);
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    uint32_t worst = 0;  // running max of |bits| per half-word; >= 0x7F80 means Inf/NaN
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+        const u32x4 w = g4[i];
+        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+        float lo[4], hi[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            lo[k] = __uint_as_float(ws[k] << 16);
+            hi[k] = __uint_as_float(ws[k] & 0xFFFF0000u);
+            const uint32_t mag_lo = ws[k] & 0x7FFFu;
+            const uint32_t mag_hi = (ws[k] >> 16) & 0x7FFFu;
+            worst = max(worst, max(mag_lo, mag_hi));
+        }
+        a0 = fmaf(lo[0], lo[0], a0);
+        a1 = fmaf(hi[0], hi[0], a1);
+        a2 = fmaf(lo[1], lo[1], a2);
+        a3 = fmaf(hi[1], hi[1], a3);
+        a0 = fmaf(lo[2], lo[2], a0);
+        a1 = fmaf(hi[2], hi[2], a1);
+        a2 = fmaf(lo[3], lo[3], a2);
+        a3 = fmaf(hi[3], hi[3], a3);
+    }
+    double sum = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
+    // The last n % 8 elements, one lane each, in workgroup 0.
+    const int64_t t = (nvec << 3) + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < 8 && t < n) {
+        const uint32_t b = g[t];
+        const float x = __uint_as_float(b << 16);
+        sum += (double)x * (double)x;
+        worst = max(worst, b & 0x7FFFu);
+    }
+    block_fold(sum, worst >= 0x7F80u ? 1u : 0u, partials + blockIdx.x);
+}
+
+// fp32 input, 4 elements per lane per row.  Requires 16-byte alignment.
+__global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict__ g, int64_t n,
+                                                         Partial *__restrict__ partials)
+{
+    const int64_t nvec = n >> 2;
+    const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    uint32_t worst = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+        const f32x4 x = g4[i];
+        a0 = fmaf(x.x, x.x, a0);
+        a1 = fmaf(x.y, x.y, a1);
+        a2 = fmaf(x.z, x.z, a2);
+        a3 = fmaf(x.w, x.w, a3);
+        worst = max(max(worst, __float_as_uint(x.x) & 0x7FFFFFFFu),
+                    max(__float_as_uint(x.y) & 0x7FFFFFFFu,
+                        max(__float_as_uint(x.z) & 0x7FFFFFFFu, __float_as_uint(x.w) & 0x7FFFFFFFu)));
+    }
+    double sum = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
+    const int64_t t = (nvec << 2) + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < 4 && t < n) {
+        const float x = g[t];
+        sum += (double)x * (double)x;
+        worst = max(worst, __float_as_uint(x) & 0x7FFFFFFFu);
+    }
+    block_fold(sum, worst >= 0x7F800000u ? 1u : 0u, partials + blockIdx.x);
+}
+
+// Any natural alignment.
+template <bool G_BF16>
+__global__ __launch_bounds__(256) void sqnorm_scalar_kernel(const void *__restrict__ g, int64_t n,
+                                                            Partial *__restrict__ partials)
+{
+    double sum = 0.0;
+    uint32_t bad = 0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        float x;
+        if constexpr (G_BF16)
+            x = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16);
+        else
+            x = reinterpret_cast<const float *>(g)[i];
+        sum += (double)x * (double)x;
+        bad |= (__float_as_uint(x) & 0x7FFFFFFFu) >= 0x7F800000u ? 1u : 0u;
+    }
+    block_fold(sum, bad, partials + blockIdx.x);
+}
+
+// One workgroup folds `count` partials in a fixed order.  A non-finite input
+// makes the sum non-finite by itself; fp32 overflow of the final value gives inf.
+__global__ __launch_bounds__(256) void sqnorm_final_kernel(const Partial *__restrict__ partials,
+                                                           int count, float *__restrict__ sqnorm_out,
+                                                           int32_t *__restrict__ found_inf_out)
+{
+    double sum = 0.0;
+    uint32_t bad = 0;
+    for (int i = threadIdx.x; i < count; i += 256) {
+        sum += partials[i].sum;
+        bad |= partials[i].bad;
+    }
+    __shared__ Partial total;
+    block_fold(sum, bad, &total);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *sqnorm_out = (float)total.sum;
+        *found_inf_out = total.bad ? 1 : 0;
+    }
+}
+
+// Per-device workspace for the partials, allocated on first use and kept.
+static zc_status partials_buffer(Partial **out)
+{
+    static std::mutex mu;
+    static Partial *bufs[64];
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return fail(ZC_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!bufs[dev]) {
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&bufs[dev]), sizeof(Partial) * kMaxPartials);
+        if (e != hipSuccess) {
+            bufs[dev] = nullptr;
+            return hip_fail(e, "hipMalloc(reduction workspace)");
+        }
+    }
+    *out = bufs[dev];
+    return ZC_OK;
+}
+
+}  // namespace zc
+
+extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
+                                    int32_t *found_inf_out, void *hip_stream)
+{
+    using namespace zc;
+    if (n < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n is negative (%lld)", (long long)n);
+    if (n > kMaxElements)
+        return fail(ZC_ERR_UNSUPPORTED, "n exceeds 2^40 elements");
+    ZC_TRY(check_dtype(g_dtype));
+    if (!sqnorm_out || !found_inf_out)
+        return fail(ZC_ERR_INVALID_ARG, "sqnorm_out and found_inf_out must not be NULL");
+    if (!aligned_to(sqnorm_out, 4) || !aligned_to(found_inf_out, 4))
+        return fail(ZC_ERR_ALIGNMENT, "outputs must be 4-byte aligned");
+    if (n > 0 && !g)
+        return fail(ZC_ERR_INVALID_ARG, "g is NULL");
+    const bool bf16 = g_dtype == ZC_BF16;
+    if (n > 0 && !aligned_to(g, bf16 ? 2 : 4))
+        return fail(ZC_ERR_ALIGNMENT, "g is not aligned to its element size");
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    Partial *partials = nullptr;
+    ZC_TRY(partials_buffer(&partials));
+    int cus = 0;
+    ZC_TRY(num_cus(&cus));
+
+    int blocks = 0;
+    if (n > 0) {
+        const int64_t per_lane = bf16 ? 8 : 4;
+        const int64_t want = (n / per_lane + 255) / 256;
+        int64_t cap = (int64_t)cus * 8;
+        if (cap > kMaxPartials)
+            cap = kMaxPartials;
+        blocks = (int)(want < 1 ? 1 : (want > cap ? cap : want));
+        if (aligned_to(g, 16)) {
+            if (bf16)
+                hipLaunchKernelGGL(sqnorm_bf16_kernel, dim3(blocks), dim3(256), 0, stream,
+                                   static_cast<const uint16_t *>(g), n, partials);
+            else
+                hipLaunchKernelGGL(sqnorm_f32_kernel, dim3(blocks), dim3(256), 0, stream,
+                                   static_cast<const float *>(g), n, partials);
+        } else {
+            if (bf16)
+                hipLaunchKernelGGL(sqnorm_scalar_kernel<true>, dim3(blocks), dim3(256), 0, stream, g, n,
+                                   partials);
+            else
+                hipLaunchKernelGGL(sqnorm_scalar_kernel<false>, dim3(blocks), dim3(256), 0, stream, g, n,
+                                   partials);
+        }
+        ZC_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(sqnorm_final_kernel, dim3(1), dim3(256), 0, stream, partials, blocks, sqnorm_out,
+                       found_inf_out);
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
+}

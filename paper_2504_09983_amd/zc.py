@@ -1,0 +1,234 @@
+"""ctypes binding over libzc.so — argument marshalling only.
+
+Every function here has the name and meaning of the C entry point declared in
+``include/zc.h``; nothing is computed in Python.  Tensors are passed as raw
+device (or pinned-host) addresses; PyTorch is only the allocator and the source
+of the HIP stream.  If the shared library is missing or fails to load this
+module raises — there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libzc.so")
+
+OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_HIP, ERR_UNSUPPORTED, ERR_NOMEM = range(6)
+F32, BF16 = 0, 1
+ADAMW, ADAM_L2 = 0, 1
+
+_STATUS_NAMES = {0: "ZC_OK", 1: "ZC_ERR_INVALID_ARG", 2: "ZC_ERR_ALIGNMENT", 3: "ZC_ERR_HIP",
+                 4: "ZC_ERR_UNSUPPORTED", 5: "ZC_ERR_NOMEM"}
+
+
+class ZcError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+class AdamHparams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("grad_scale", ctypes.c_float), ("step", ctypes.c_int64),
+                ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class Segment(ctypes.Structure):
+    _fields_ = [("src_offset", ctypes.c_int64), ("dst", ctypes.c_void_p),
+                ("numel", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libzc.so once; raise if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with "
+                          "`python -m paper_2504_09983_amd.build` (hipcc, gfx950)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    L.zc_version.restype = ctypes.c_int
+    L.zc_version.argtypes = []
+    L.zc_last_error.restype = ctypes.c_char_p
+    L.zc_last_error.argtypes = []
+    L.zc_adam_step.restype = ctypes.c_int
+    L.zc_adam_step.argtypes = [vp, vp, vp, vp, ctypes.c_int, i64, ctypes.POINTER(AdamHparams),
+                               vp, vp, vp]
+    L.zc_cast_bf16.restype = ctypes.c_int
+    L.zc_cast_bf16.argtypes = [vp, vp, i64, vp]
+    L.zc_flat_layout.restype = ctypes.c_int
+    L.zc_flat_layout.argtypes = [ctypes.POINTER(i64), i64, i32, i64, ctypes.POINTER(i64),
+                                 ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.zc_unshard_plan_create.restype = ctypes.c_int
+    L.zc_unshard_plan_create.argtypes = [ctypes.POINTER(Segment), i64, i64, ctypes.POINTER(vp)]
+    L.zc_unshard.restype = ctypes.c_int
+    L.zc_unshard.argtypes = [vp, vp, vp]
+    L.zc_unshard_plan_destroy.restype = ctypes.c_int
+    L.zc_unshard_plan_destroy.argtypes = [vp]
+    L.zc_offload_create.restype = ctypes.c_int
+    L.zc_offload_create.argtypes = [i64, i32, ctypes.POINTER(vp)]
+    L.zc_offload_adam_step.restype = ctypes.c_int
+    L.zc_offload_adam_step.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, ctypes.c_int,
+                                       ctypes.POINTER(AdamHparams), vp, vp, vp]
+    L.zc_offload_destroy.restype = ctypes.c_int
+    L.zc_offload_destroy.argtypes = [vp]
+    L.zc_grad_sqnorm.restype = ctypes.c_int
+    L.zc_grad_sqnorm.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp]
+    L.zc_tune_set.restype = ctypes.c_int
+    L.zc_tune_set.argtypes = [ctypes.c_char_p, i64]
+    L.zc_tune_get.restype = ctypes.c_int
+    L.zc_tune_get.argtypes = [ctypes.c_char_p, ctypes.POINTER(i64)]
+    _lib = L
+    return L
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise ZcError(status, lib().zc_last_error().decode("utf-8", "replace"))
+
+
+def _addr(x) -> Optional[int]:
+    """Address of a torch tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    raise TypeError(f"cannot take the address of {type(x)!r}")
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream  # a hipStream_t on ROCm
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def hparams(*, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0, mode=ADAMW) -> AdamHparams:
+    return AdamHparams(lr, beta1, beta2, eps, weight_decay, grad_scale, int(step), int(mode), 0)
+
+
+def version() -> int:
+    return lib().zc_version()
+
+
+def last_error() -> str:
+    return lib().zc_last_error().decode("utf-8", "replace")
+
+
+def adam_step(p, m, v, g, g_dtype: int, n: int, hp: AdamHparams, bf16_out=None, skip_flag=None,
+              stream=None) -> None:
+    _check(lib().zc_adam_step(_addr(p), _addr(m), _addr(v), _addr(g), g_dtype, n,
+                              ctypes.byref(hp), _addr(bf16_out), _addr(skip_flag),
+                              _stream(stream)))
+
+
+def cast_bf16(src, dst, n: int, stream=None) -> None:
+    _check(lib().zc_cast_bf16(_addr(src), _addr(dst), n, _stream(stream)))
+
+
+def flat_layout(numels: Sequence[int], world: int, shard_align: int = 1):
+    """(offsets list, shard_numel, total) computed by the C library on the host."""
+    k = len(numels)
+    arr = (ctypes.c_int64 * max(1, k))(*[int(x) for x in numels])
+    offs = (ctypes.c_int64 * max(1, k))()
+    shard = ctypes.c_int64(0)
+    total = ctypes.c_int64(0)
+    _check(lib().zc_flat_layout(arr, k, world, shard_align, offs, ctypes.byref(shard),
+                                ctypes.byref(total)))
+    return [offs[i] for i in range(k)], shard.value, total.value
+
+
+class UnshardPlan:
+    """Owns a zc_unshard_plan; segments are (src_offset, dst address or tensor, numel)."""
+
+    def __init__(self, segments, gathered_numel: int):
+        segs = [(int(o), _addr(d) or 0, int(n)) for o, d, n in segments]
+        arr = (Segment * max(1, len(segs)))(*[Segment(o, d if d else None, n) for o, d, n in segs])
+        handle = ctypes.c_void_p(None)
+        _check(lib().zc_unshard_plan_create(arr, len(segs), gathered_numel, ctypes.byref(handle)))
+        self._h = handle
+
+    def run(self, gathered, stream=None) -> None:
+        _check(lib().zc_unshard(self._h, _addr(gathered), _stream(stream)))
+
+    def destroy(self) -> None:
+        if self._h is not None and self._h.value is not None:
+            _check(lib().zc_unshard_plan_destroy(self._h))
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def unshard_plan_create(segments, gathered_numel: int) -> UnshardPlan:
+    return UnshardPlan(segments, gathered_numel)
+
+
+def unshard(plan: UnshardPlan, gathered, stream=None) -> None:
+    plan.run(gathered, stream)
+
+
+class OffloadCtx:
+    """Owns a zc_offload_ctx (staging ring, copy streams, events)."""
+
+    def __init__(self, chunk_bytes: int = 64 << 20, num_buffers: int = 3):
+        handle = ctypes.c_void_p(None)
+        _check(lib().zc_offload_create(chunk_bytes, num_buffers, ctypes.byref(handle)))
+        self._h = handle
+        self.chunk_bytes = chunk_bytes
+        self.num_buffers = num_buffers
+
+    def adam_step(self, p_dev, m_dev, v_dev, n_resident: int, p_host, m_host, v_host,
+                  n_streamed: int, g_dev, g_dtype: int, hp: AdamHparams, bf16_out_dev=None,
+                  skip_flag=None, stream=None) -> None:
+        _check(lib().zc_offload_adam_step(self._h, _addr(p_dev), _addr(m_dev), _addr(v_dev),
+                                          n_resident, _addr(p_host), _addr(m_host), _addr(v_host),
+                                          n_streamed, _addr(g_dev), g_dtype, ctypes.byref(hp),
+                                          _addr(bf16_out_dev), _addr(skip_flag), _stream(stream)))
+
+    def destroy(self) -> None:
+        if self._h is not None and self._h.value is not None:
+            _check(lib().zc_offload_destroy(self._h))
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def offload_create(chunk_bytes: int = 64 << 20, num_buffers: int = 3) -> OffloadCtx:
+    return OffloadCtx(chunk_bytes, num_buffers)
+
+
+def grad_sqnorm(g, g_dtype: int, n: int, sqnorm_out, found_inf_out, stream=None) -> None:
+    _check(lib().zc_grad_sqnorm(_addr(g), g_dtype, n, _addr(sqnorm_out), _addr(found_inf_out),
+                                _stream(stream)))
+
+
+def tune_set(key: str, value: int) -> None:
+    _check(lib().zc_tune_set(key.encode(), int(value)))
+
+
+def tune_get(key: str) -> int:
+    out = ctypes.c_int64(0)
+    _check(lib().zc_tune_get(key.encode(), ctypes.byref(out)))
+    return out.value

@@ -1,0 +1,128 @@
+"""GPU parity: the offloaded step.  Chunking and overlap must not change a bit
+against the resident GPU step (elements are independent); the resident step
+carries the floating-point tolerance against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_09983_amd import synth, zc
+from tests.gpu_util import DEV, HP, assert_state_close, dev_f32, dev_u16, host_f32, host_u16, sync
+
+pytestmark = pytest.mark.gpu
+
+
+def pinned(a: np.ndarray) -> torch.Tensor:
+    t = torch.empty(a.size, dtype=torch.float32, pin_memory=True)
+    t.numpy()[:] = a
+    return t
+
+
+def offload_vs_resident(n, n_res, chunk_bytes, nbuf, steps=2, g_bf16=True, zero_copy=False):
+    p0 = synth.host_params(n, 21)
+    m0 = synth.host_normal(n, 1e-4, 22)
+    v0 = np.abs(synth.host_normal(n, 1e-7, 23))
+    # resident reference on the GPU
+    rp, rm, rv = dev_f32(p0), dev_f32(m0), dev_f32(v0)
+    rout = torch.zeros(n, dtype=torch.int16, device=DEV)
+    # offloaded state
+    dp, dm, dv = dev_f32(p0[:n_res]), dev_f32(m0[:n_res]), dev_f32(v0[:n_res])
+    hp_, hm_, hv_ = pinned(p0[n_res:]), pinned(m0[n_res:]), pinned(v0[n_res:])
+    oout = torch.zeros(n, dtype=torch.int16, device=DEV)
+    # oracle state
+    op, om, ov = p0.copy(), m0.copy(), v0.copy()
+    oo = np.zeros(n, np.uint16)
+
+    ctx = zc.offload_create(chunk_bytes, nbuf)
+    old = zc.tune_get("offload.zero_copy")
+    zc.tune_set("offload.zero_copy", 1 if zero_copy else 0)
+    try:
+        for t in range(1, steps + 1):
+            g = synth.host_grads_f32(n, t)
+            if g_bf16:
+                g = oracle.cast_bf16(g)
+                dg = dev_u16(g)
+            else:
+                dg = dev_f32(g)
+            dt = zc.BF16 if g_bf16 else zc.F32
+            hp = zc.hparams(step=t, **HP)
+            zc.adam_step(rp, rm, rv, dg, dt, n, hp, bf16_out=rout)
+            ctx.adam_step(dp if n_res else None, dm if n_res else None, dv if n_res else None, n_res,
+                          hp_ if n > n_res else None, hm_ if n > n_res else None,
+                          hv_ if n > n_res else None, n - n_res, dg, dt, hp, bf16_out_dev=oout)
+            oracle.adam_step(op, om, ov, g, step=t, bf16_out=oo, **HP)
+        sync()
+    finally:
+        zc.tune_set("offload.zero_copy", old)
+        ctx.destroy()
+    for res, dev_part, host_part in ((rp, dp, hp_), (rm, dm, hm_), (rv, dv, hv_)):
+        r = host_f32(res)
+        assert np.array_equal(r[:n_res].view(np.uint32), host_f32(dev_part).view(np.uint32))
+        assert np.array_equal(r[n_res:].view(np.uint32), host_part.numpy().view(np.uint32))
+    assert torch.equal(rout, oout)
+    assert_state_close(host_f32(rp), host_f32(rm), host_f32(rv), op, om, ov, tag="offload")
+    assert np.array_equal(host_u16(oout), oracle.cast_bf16(host_f32(rp)))
+
+
+@pytest.mark.parametrize("frac", [0.0, 0.25, 0.5, 1.0])
+def test_offload_equals_resident_fractions(frac):
+    n = 3 * (1 << 20) + 4099
+    n_res = int(frac * n) // 1024 * 1024
+    offload_vs_resident(n, n_res, 1 << 20, 3)
+
+
+@pytest.mark.parametrize("nbuf", [1, 2, 3, 5])
+@pytest.mark.parametrize("chunk_bytes", [4096, 1 << 16])
+def test_offload_ring_sizes(nbuf, chunk_bytes):
+    # many chunks through few slots: every slot is reused several times
+    n = 40 * (chunk_bytes // 4) // 3 + 17
+    offload_vs_resident(n, 1024, chunk_bytes, nbuf, steps=2)
+
+
+def test_offload_fp32_grads_and_single_partial_chunk():
+    offload_vs_resident(1000, 0, 1 << 20, 3, g_bf16=False)       # one partial chunk
+    offload_vs_resident((1 << 18), 0, 1 << 20, 2, g_bf16=False)  # exactly one full chunk
+
+
+def test_offload_64mib_chunks():
+    """The reference chunk size: 64 MiB per array, 3 slots, 2.5 chunks."""
+    n = (16 << 20) * 2 + (8 << 20) + 5
+    offload_vs_resident(n, 0, 64 << 20, 3, steps=1)
+
+
+def test_offload_zero_copy_mode():
+    offload_vs_resident((1 << 20) + 77, 4096, 1 << 20, 3, zero_copy=True)
+
+
+def test_offload_rejects_unpinned_host_memory():
+    n = 4096
+    ctx = zc.offload_create(1 << 16, 2)
+    pageable = [torch.zeros(n, dtype=torch.float32) for _ in range(3)]
+    dg = torch.zeros(n, dtype=torch.int16, device=DEV)
+    with pytest.raises(zc.ZcError) as ei:
+        ctx.adam_step(None, None, None, 0, *pageable, n, dg, zc.BF16, zc.hparams(step=1, **HP))
+    assert ei.value.status == zc.ERR_INVALID_ARG and "pinned" in ei.value.message
+    # the context is still usable afterwards
+    pin = [torch.zeros(n, dtype=torch.float32, pin_memory=True) for _ in range(3)]
+    ctx.adam_step(None, None, None, 0, *pin, n, dg, zc.BF16, zc.hparams(step=1, **HP))
+    sync()
+    ctx.destroy()
+
+
+def test_resume_after_round_trip_through_host():
+    """5 + 5 steps with the state copied to the host and back in between == 10 steps."""
+    n = 50000
+    p0 = synth.host_params(n, 31)
+    a = [dev_f32(p0), dev_f32(np.zeros(n)), dev_f32(np.zeros(n))]
+    b = [t.clone() for t in a]
+    for t in range(1, 11):
+        dg = dev_f32(synth.host_grads_f32(n, t))
+        hp = zc.hparams(step=t, **HP)
+        zc.adam_step(*a, dg, zc.F32, n, hp)
+        zc.adam_step(*b, dg, zc.F32, n, hp)
+        if t == 5:
+            sync()
+            b = [x.cpu().to(DEV) for x in b]
+    sync()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)

@@ -1,0 +1,143 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header
+declares, rejects bad arguments before touching a GPU, and its host-only layout
+helper agrees with the oracle's layout."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle.layout as olayout
+from paper_2504_09983_amd import synth, zc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "zc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(zc_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = zc.lib()
+    names = declared_functions()
+    assert {"zc_adam_step", "zc_cast_bf16", "zc_unshard", "zc_offload_adam_step",
+            "zc_unshard_plan_create", "zc_unshard_plan_destroy", "zc_offload_create",
+            "zc_offload_destroy", "zc_grad_sqnorm", "zc_flat_layout", "zc_last_error",
+            "zc_version", "zc_tune_set", "zc_tune_get"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert zc.version() >= 100
+
+
+def test_hparams_struct_layout_matches_header():
+    # float x6, int64, int32 x2 -> 40 bytes with the int64 at offset 24
+    assert ctypes.sizeof(zc.AdamHparams) == 40
+    assert zc.AdamHparams.step.offset == 24 and zc.AdamHparams.mode.offset == 32
+    assert ctypes.sizeof(zc.Segment) == 24
+
+
+HP = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(zc.ZcError) as ei:
+        fn(*a, **k)
+    return ei.value.status
+
+
+def test_adam_step_rejects_bad_arguments_without_a_gpu():
+    hp = zc.hparams(step=1, **HP)
+    A = 0x10000  # fake, never dereferenced: validation fails first
+    assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, -1, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step, 0, A + 64, A + 128, A + 192, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step, A, A + 64, A + 128, 0, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step, A + 2, A + 64, A + 128, A + 192, zc.F32, 8, hp, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.adam_step, A, A + 64, A + 128, A + 193, zc.BF16, 8, hp, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, 8, hp, bf16_out=A + 257, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.adam_step, A, A, A + 128, A + 192, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, 7, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, (1 << 40) + 1, hp, stream=0) == zc.ERR_UNSUPPORTED
+    for bad in (dict(step=0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0),
+                dict(lr=float("nan")), dict(mode=3), dict(grad_scale=float("inf")),
+                dict(weight_decay=float("nan"))):
+        kw = dict(HP, step=1)
+        kw.update(bad)
+        assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, 8, zc.hparams(**kw), stream=0) == zc.ERR_INVALID_ARG
+    assert "mode" in zc.last_error() or "weight_decay" in zc.last_error()
+    # n == 0 is a no-op even with NULL pointers
+    zc.adam_step(0, 0, 0, 0, zc.F32, 0, hp, stream=0)
+
+
+def test_cast_and_sqnorm_reject_bad_arguments_without_a_gpu():
+    A = 0x20000
+    assert _status(zc.cast_bf16, A, A + 4096, -5, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.cast_bf16, 0, A, 4, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.cast_bf16, A + 1, A + 4096, 4, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.cast_bf16, A, A + 4097, 4, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.cast_bf16, A, A + 8, 16, stream=0) == zc.ERR_INVALID_ARG   # overlap
+    zc.cast_bf16(0, 0, 0, stream=0)
+    assert _status(zc.grad_sqnorm, A, zc.BF16, -1, A + 64, A + 68, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.grad_sqnorm, A, zc.BF16, 4, 0, A + 68, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.grad_sqnorm, A + 1, zc.BF16, 4, A + 64, A + 68, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.grad_sqnorm, 0, zc.F32, 4, A + 64, A + 68, stream=0) == zc.ERR_INVALID_ARG
+
+
+def test_unshard_plan_and_offload_reject_bad_arguments_without_a_gpu():
+    A = 0x30000
+    assert _status(zc.UnshardPlan, [(-1, A, 4)], 100) == zc.ERR_INVALID_ARG
+    assert _status(zc.UnshardPlan, [(98, A, 4)], 100) == zc.ERR_INVALID_ARG
+    assert _status(zc.UnshardPlan, [(0, A, -4)], 100) == zc.ERR_INVALID_ARG
+    assert _status(zc.UnshardPlan, [(0, 0, 4)], 100) == zc.ERR_INVALID_ARG
+    assert _status(zc.UnshardPlan, [(0, A + 1, 4)], 100) == zc.ERR_ALIGNMENT
+    assert _status(zc.UnshardPlan, [(0, A, 4)], -1) == zc.ERR_INVALID_ARG
+    assert "segment" in zc.last_error() or "gathered" in zc.last_error()
+    assert _status(zc.OffloadCtx, 1000, 3) == zc.ERR_INVALID_ARG
+    assert _status(zc.OffloadCtx, 1 << 20, 0) == zc.ERR_INVALID_ARG
+    assert _status(zc.OffloadCtx, 1 << 20, 9) == zc.ERR_INVALID_ARG
+    assert _status(zc.OffloadCtx, 0, 3) == zc.ERR_INVALID_ARG
+
+
+def test_tune_knobs():
+    old = zc.tune_get("adam.rows")
+    zc.tune_set("adam.rows", 4)
+    assert zc.tune_get("adam.rows") == 4
+    assert _status(zc.tune_set, "adam.rows", 3) == zc.ERR_INVALID_ARG
+    assert _status(zc.tune_set, "adam.rows", 9) == zc.ERR_INVALID_ARG
+    assert _status(zc.tune_set, "no.such.key", 1) == zc.ERR_INVALID_ARG
+    assert _status(zc.tune_get, "no.such.key") == zc.ERR_INVALID_ARG
+    zc.tune_set("adam.rows", old)
+
+
+@pytest.mark.parametrize("align", [1, 8, 4096])
+def test_flat_layout_matches_oracle_layout(align):
+    for numels in ([1, 3, 7, 4097], [0, 9, 0, 2], [], [4096] * 5 + [17],
+                   synth.tensor_numels(synth.LLAMA3_8B), synth.tensor_numels(synth.MIXTRAL_8X7B),
+                   synth.tensor_numels(synth.LLAMA3_70B)):
+        offs, shard, total = zc.flat_layout(numels, 8, align)
+        o_offs, o_shard, o_total = olayout.flat_layout(numels, 8, align)
+        assert offs == list(o_offs) and shard == o_shard and total == o_total
+
+
+def test_flat_layout_rejects_bad_input():
+    assert _status(zc.flat_layout, [4, -1], 8, 1) == zc.ERR_INVALID_ARG
+    assert _status(zc.flat_layout, [4], 0, 1) == zc.ERR_INVALID_ARG
+    assert _status(zc.flat_layout, [4], 8, 0) == zc.ERR_INVALID_ARG
+    assert _status(zc.flat_layout, [1 << 45, 1 << 45, 1 << 45], 8, 1) == zc.ERR_UNSUPPORTED
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2504_09983_amd")
+    for dirpath, _dirs, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "zc_oracle" not in text and "zco_" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2504_09983_amd" not in text and "zc.h" not in text, f
