@@ -53,6 +53,10 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with "
                           "`python -m paper_2504_09983_amd.build` (hipcc, gfx950)")
+    # One HIP runtime per process: PyTorch (the allocator and stream source) ships its
+    # own libamdhip64 and must map it first, so that libzc binds to that same instance
+    # instead of bringing in a second runtime that knows nothing of torch's streams.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     L.zc_version.restype = ctypes.c_int
