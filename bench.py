@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of one rank's sharded mixed-precision optimizer step on one MI355X.
+
+A *step* is one pass of the whole hot path over one batch of synthetic input:
+
+    zc_grad_sqnorm   (overflow flag + squared norm of the bf16 gradient shard)
+    zc_adam_step     (fused AdamW over the fp32 shard, bf16 copy written straight
+                      into this rank's slot of the gathered buffer, skipped on overflow)
+    zc_unshard       (gathered flat bf16 buffer of 8 rank shards -> per-layer tensors)
+
+on a one-of-8 shard of a Llama-3-8B-shaped model (1,003,782,656 fp32 elements,
+291 tensors, boundaries not aligned to the shards).  Everything is resident in
+HBM when the timed region starts.  Prints ONE JSON line.
+
+Extra legs outside the timed region: the offloaded step (pinned host p/m/v
+streamed through a 3-slot ring) and the CPU oracle on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+PCIE_PEAK_GBS = 63.0           # Gen5 x16, per direction
+WORLD = 8
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b",
+                    choices=["llama3_8b", "llama3_70b", "mixtral_8x7b", "tiny"])
+    ap.add_argument("--no-unshard", action="store_true",
+                    help="leave the unshard copy out (needed for 70B/Mixtral to fit with the step)")
+    ap.add_argument("--offload-elems", type=int, default=1 << 28,
+                    help="elements streamed in the offload leg (0 = skip the leg)")
+    ap.add_argument("--offload-frac", type=float, default=0.0, help="resident fraction f")
+    ap.add_argument("--offload-chunk-mib", type=int, default=64)
+    ap.add_argument("--offload-buffers", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain copy of known size (one unshard segment of 2^30 bf16 "
+                         "elements, 2 GiB read + 2 GiB written, 5 launches): the reference for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="tuning knob, e.g. adam.rows=4 (repeatable)")
+    return ap.parse_args()
+
+
+def gb(x):
+    return x / 1e9
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path (one rank's share of the step, the other "
+              "ranks' bytes synthesised locally); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_09983_amd import synth, zc
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    for kv in args.tune:
+        k, val = kv.split("=")
+        zc.tune_set(k, int(val))
+
+    if args.calibrate_copy:
+        k = 1 << 30
+        src = torch.empty(k, dtype=torch.int16, device=dev)
+        dst = torch.empty(k, dtype=torch.int16, device=dev)
+        synth.device_index_hash16_(src)
+        plan = zc.unshard_plan_create([(0, dst, k)], k)
+        for _ in range(5):
+            zc.unshard(plan, src)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+        print(json.dumps({"calibrate_copy": {"kernel": "zc::unshard_kernel", "launches": 5,
+                                             "read_bytes_per_launch": 2 * k,
+                                             "written_bytes_per_launch": 2 * k}}))
+        return
+
+    # ---- workload ------------------------------------------------------------------
+    if args.workload == "tiny":
+        tensors = synth.TINY_TENSORS
+    else:
+        tensors = synth.tensor_list(synth.SHAPES[args.workload])
+    numels = [int(__import__("numpy").prod(d)) for _, d in tensors]
+    offs, shard, total = zc.flat_layout(numels, WORLD, 1)
+    n = shard
+    do_unshard = not args.no_unshard
+    hp_kw = dict(synth.HP)
+
+    p = torch.empty(n, dtype=torch.float32, device=dev)
+    m = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    g = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    synth.device_normal_(p, synth.P_STD, seed=2)
+    synth.device_normal_(g, synth.G_STD, seed=2001)
+    norm = torch.zeros(1, dtype=torch.float32, device=dev)
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    if do_unshard:
+        gathered = torch.empty(WORLD * shard, dtype=torch.int16, device=dev)
+        synth.device_index_hash16_(gathered)          # the other 7 ranks' bytes
+        send = gathered[:n]                            # this rank's slot (rank 0)
+        outs = [torch.empty(d, dtype=torch.bfloat16, device=dev) for _, d in tensors]
+        plan = zc.unshard_plan_create([(o, t, k) for o, t, k in zip(offs, outs, numels)],
+                                      WORLD * shard)
+    else:
+        send = torch.empty(n, dtype=torch.int16, device=dev)
+    torch.cuda.synchronize()
+
+    step_no = [0]
+
+    def one_step(ev=None):
+        step_no[0] += 1
+        hp = zc.hparams(step=step_no[0], **hp_kw)
+        if ev: ev[0].record()
+        zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
+        if ev: ev[1].record()
+        zc.adam_step(p, m, v, g, zc.BF16, n, hp, bf16_out=send, skip_flag=flag)
+        if ev: ev[2].record()
+        if do_unshard:
+            zc.unshard(plan, gathered)
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    def avg(i):
+        return sum(e[i].elapsed_time(e[i + 1]) for e in events) / len(events)
+
+    t_norm, t_adam, t_unshard = avg(0), avg(1), avg(2)
+    assert flag.item() == 0, "synthetic gradients must be finite"
+
+    kernels = {
+        "sqnorm": dict(name="zc::sqnorm_bf16_kernel", ms=t_norm, bytes=2 * n, units=n,
+                       bytes_per_unit=2),
+        "adam": dict(name="zc::adam_vec_kernel", ms=t_adam, bytes=28 * n, units=n,
+                     bytes_per_unit=28),
+    }
+    if do_unshard:
+        kernels["unshard"] = dict(name="zc::unshard_kernel", ms=t_unshard, bytes=4 * total,
+                                  units=total, bytes_per_unit=4)
+    for kd in kernels.values():
+        kd["GBps"] = gb(kd["bytes"]) / (kd["ms"] * 1e-3)
+        kd["frac"] = kd["GBps"] / HBM_PEAK_GBS
+    dominant = max(kernels, key=lambda k: kernels[k]["ms"])
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            tj = json.load(open(tpath))
+            rec = tj.get(args.workload, {}).get(dominant)
+            if rec:
+                traffic = rec["fetch_bytes"] + rec["write_bytes"]
+        except Exception:
+            traffic = None
+
+    roofline = dict(bound="hbm", kernel=kernels[dominant]["name"],
+                    achieved=round(kernels[dominant]["GBps"], 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(kernels[dominant]["frac"], 4), traffic=traffic,
+                    algorithmic_bytes_per_launch=kernels[dominant]["bytes"],
+                    avg_launch_ms=round(kernels[dominant]["ms"], 4))
+
+    result = {
+        "metric": "optimizer-step Gparams/s per shard",
+        "value": round(n / (ms_per_step * 1e-3) / 1e9, 3),
+        "unit": "Gparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {0: "f32", 1: "f32+f64", 2: "f64"}[zc.tune_get("adam.arith")], "data": "synthetic",
+        "config": {
+            "workload": (f"{args.workload} one-of-{WORLD} shard: grad-norm + fused AdamW with bf16 copy"
+                         + (" + unshard of the 8-shard gathered buffer" if do_unshard else "")),
+            "shard_elements": n, "model_elements": total, "tensors": len(numels),
+            "grads": "bf16", "state": "fp32 p/m/v resident in HBM",
+            "tuning": {k: zc.tune_get(k) for k in ("adam.arith", "adam.block", "adam.rows",
+                                                  "adam.waves_per_cu", "adam.nontemporal",
+                                                  "copy.waves_per_cu", "copy.nontemporal")},
+        },
+        "roofline": roofline,
+        "kernels": {k: dict(ms=round(d["ms"], 4), GBps=round(d["GBps"], 1), frac=round(d["frac"], 4),
+                            algorithmic_bytes=d["bytes"],
+                            rate_G_per_s=round(d["units"] / (d["ms"] * 1e-3) / 1e9, 2))
+                    for k, d in kernels.items()},
+        "adam_step_gparams_per_s": round(n / (t_adam * 1e-3) / 1e9, 2),
+    }
+
+    # ---- free the resident workload before the extra legs --------------------------
+    if do_unshard:
+        plan.destroy()
+        del outs, gathered
+    del p, m, v, g, send
+    torch.cuda.empty_cache()
+
+    if args.offload_elems > 0:
+        result["offload"] = offload_leg(torch, synth, zc, dev, args)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline_leg(synth)
+    print(json.dumps(result))
+
+
+def offload_leg(torch, synth, zc, dev, args):
+    """Offloaded step: p/m/v of the streamed part in pinned host DRAM, 3-slot ring."""
+    n = int(args.offload_elems)
+    n_res = int(args.offload_frac * n) // 1024 * 1024
+    n_str = n - n_res
+    chunk = args.offload_chunk_mib << 20
+    hp_, hm_, hv_ = (torch.empty(n_str, dtype=torch.float32, pin_memory=True) for _ in range(3))
+    tmp = torch.empty(n_str, dtype=torch.float32, device=dev)
+    synth.device_normal_(tmp, synth.P_STD, seed=3)
+    hp_.copy_(tmp)
+    hm_.zero_()
+    hv_.zero_()
+    del tmp
+    dp, dm, dv = (torch.zeros(max(n_res, 1), dtype=torch.float32, device=dev) for _ in range(3))
+    g = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    synth.device_normal_(g, synth.G_STD, seed=2002)
+    send = torch.empty(n, dtype=torch.int16, device=dev)
+    ctx = zc.offload_create(chunk, args.offload_buffers)
+    torch.cuda.synchronize()
+
+    def run(step):
+        ctx.adam_step(dp if n_res else None, dm if n_res else None, dv if n_res else None, n_res,
+                      hp_, hm_, hv_, n_str, g, zc.BF16, zc.hparams(step=step, **synth.HP),
+                      bf16_out_dev=send)
+
+    run(1)
+    torch.cuda.synchronize()
+    reps = 3
+    t0 = time.perf_counter()
+    for k in range(reps):
+        run(2 + k)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+
+    # plain pinned-copy ceilings with the same chunking: one direction at a time and both
+    nbytes = 4 * n_str
+    t_h2d = min(ctx.probe_link(hp_, hv_, nbytes, 0) for _ in range(3)) * 1e-3
+    t_d2h = min(ctx.probe_link(hp_, hv_, nbytes, 1) for _ in range(3)) * 1e-3
+    t_both = min(ctx.probe_link(hp_, hv_, nbytes, 2) for _ in range(3)) * 1e-3
+    ctx.destroy()
+    one_way = 12 * n_str
+    return {
+        "elements": n, "resident_fraction": n_res / n, "chunk_MiB": args.offload_chunk_mib,
+        "buffers": args.offload_buffers, "ms_per_step": round(dt * 1e3, 3),
+        "gparams_per_s": round(n / dt / 1e9, 3),
+        "link_GBps_each_direction": round(gb(one_way) / dt, 2),
+        "link_peak_GBps": PCIE_PEAK_GBS, "frac_of_link_peak": round(gb(one_way) / dt / PCIE_PEAK_GBS, 4),
+        "memcpy_ceiling_GBps": {"h2d": round(gb(4 * n_str) / t_h2d, 2),
+                                "d2h": round(gb(4 * n_str) / t_d2h, 2),
+                                "both_each": round(gb(4 * n_str) / t_both, 2)},
+        "zero_copy": zc.tune_get("offload.zero_copy"),
+    }
+
+
+def cpu_baseline_leg(synth):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+
+    ns = 1 << 26                                   # shard sample; gathered sample = 8x that
+    passes = 16
+    p = synth.host_params(ns, 2)
+    m = np.zeros(ns, np.float32)
+    v = np.zeros(ns, np.float32)
+    g = oracle.cast_bf16(synth.host_normal(ns, synth.G_STD, 2001))
+    gathered = synth.host_index_hash16(0, WORLD * ns)
+    send = gathered[:ns]
+    # tensor boundaries: the 8B model's first tensors scaled into the sample
+    cuts = [0, ns // 3 + 5, ns * 2 + 17, ns * 5 - 3, WORLD * ns]
+    offs = cuts[:-1]
+    nums = [b - a for a, b in zip(cuts[:-1], cuts[1:])]
+    t0 = time.perf_counter()
+    for t in range(1, passes + 1):
+        _, bad = oracle.grad_sqnorm(g)
+        oracle.adam_step(p, m, v, g, step=t, bf16_out=send, skip=bool(bad), **synth.HP)
+        oracle.unshard(gathered, offs, nums)
+    dt = (time.perf_counter() - t0) / passes
+    return {"value": round(ns / dt / 1e9, 4), "unit": "Gparams/s", "cores": 1, "kind": "oracle",
+            "sample": (f"{passes} passes over a 2^26-element shard slice (grad-norm + AdamW + bf16 "
+                       f"copy) and its 8 x 2^26-element gathered buffer (unshard); "
+                       f"{round(dt, 2)} s per pass; host has {os.cpu_count()} logical CPUs, "
+                       "the oracle is sequential"),
+            "seconds": round(dt * passes, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -179,6 +179,17 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
 zc_status zc_offload_destroy(zc_offload_ctx *ctx);
 
 /*
+ * Measurement helper: the practical host-link ceiling next to which the offloaded
+ * step is reported.  Copies `bytes` from pinned HOST memory into the context's
+ * staging ring (mode 0), from the ring to pinned HOST memory (mode 1), or both at
+ * once on the context's two copy streams (mode 2), in chunk_bytes pieces, and
+ * returns the wall time in *ms_out (HOST).  Blocks until the copies are done.
+ * The data copied is meaningless; host_src is only read, host_dst only written.
+ */
+zc_status zc_offload_probe_link(zc_offload_ctx *ctx, const void *host_src, void *host_dst,
+                                int64_t bytes, int32_t mode, float *ms_out);
+
+/*
  * Squared L2 norm of the gradient partition and a non-finite flag (the
  * overflow check and clipping input that precede a mixed-precision step; not
  * in the paper, which only states that fp32 gradients are kept).
@@ -192,13 +203,15 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
 /*
  * Tuning knobs for measurement sweeps (process-wide, not thread-safe against
  * concurrent launches).  Unknown key -> ZC_ERR_INVALID_ARG.  Keys:
- *   "adam.rows"        rows of 4 elements per lane per tile: 1, 2 or 4
- *   "adam.blocks_per_cu" 0 = one tile per workgroup, k>0 = persistent grid of
- *                      k workgroups per CU striding over tiles
+ *   "adam.rows"        128-bit vectors per lane per tile: 1, 2 or 4
+ *   "adam.block"       threads per workgroup: 64, 128 or 256
+ *   "adam.waves_per_cu" cap on resident waves per compute unit, enforced through an
+ *                      unused dynamic-LDS request; 0 = no cap
  *   "adam.nontemporal" 0/1 non-temporal loads and stores
  *   "adam.arith"       0 = fp32 only, 1 = fp64 multiply-adds with fp32 sqrt/div,
  *                      2 = fp64 throughout
- *   "copy.blocks_per_cu", "copy.nontemporal"   same for cast and unshard
+ *   "copy.waves_per_cu", "cast.waves_per_cu"  the same cap for unshard and for the cast
+ *   "copy.nontemporal"  non-temporal accesses in cast and unshard
  *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host
  */
 zc_status zc_tune_set(const char *key, int64_t value);

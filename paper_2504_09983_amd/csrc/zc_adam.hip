@@ -4,8 +4,12 @@
 // read once and p, m, v (+ bf16 p) written once.  Nothing is reused, nothing is
 // a contraction, so the kernel is HBM-bound and built around 128-bit accesses:
 // a wave reads one contiguous 1 KiB row per instruction (lane l owns elements
-// 4l..4l+3 of the row), a 256-thread workgroup owns ROWS rows of 1024
-// elements per tile, and all loads of a tile are issued before any arithmetic.
+// 4l..4l+3 of the row), a workgroup owns ROWS rows of 4*BLOCK elements, and
+// all loads of a tile are issued before any arithmetic.  Measured on MI355X the
+// mixed read/write stream runs fastest with small workgroups (one or two
+// waves) and only ~8-12 waves resident per CU; more waves in flight widen the
+// window of DRAM pages touched at once and cost bandwidth.  The resident-wave
+// count is capped by asking for a slice of LDS that is never used.
 //
 // The arithmetic (paper: Adam with momentum and variance buffers in fp32 next
 // to fp32 master parameters; Experimental settings, Adaptive offloading) is
@@ -124,16 +128,19 @@ __device__ __forceinline__ void st(T *ptr, T val)
         *ptr = val;
 }
 
-template <int ROWS, bool G_BF16, bool NT, int ARITH, bool GUARD>
+template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH, bool GUARD>
 __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restrict__ m4,
                                           f32x4 *__restrict__ v4, const void *__restrict__ g,
                                           u32x2 *__restrict__ out2, int64_t first, int64_t nvec,
-                                          const AdamScalars &s)
+                                          const AdamScalars &s, const int32_t *__restrict__ skip)
 {
+    // The skip flag is fetched together with the data and only tested before the
+    // first store, so its latency hides behind the tile's own loads.
+    const int32_t skip_now = skip ? *skip : 0;
     f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int64_t i = first + (int64_t)r * 256;
+        const int64_t i = first + (int64_t)r * BLOCK;
         if (!GUARD || i < nvec) {
             pv[r] = ld<NT>(p4 + i);
             mv[r] = ld<NT>(m4 + i);
@@ -149,9 +156,11 @@ __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restr
             }
         }
     }
+    if (skip_now != 0)
+        return;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int64_t i = first + (int64_t)r * 256;
+        const int64_t i = first + (int64_t)r * BLOCK;
         if (!GUARD || i < nvec) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -174,35 +183,35 @@ __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restr
     }
 }
 
-// Requires p, m, v 16-byte aligned and g, out aligned to 4 elements.
-template <int ROWS, bool G_BF16, bool NT, int ARITH>
-__global__ __launch_bounds__(256) void adam_vec_kernel(float *__restrict__ p, float *__restrict__ m,
-                                                       float *__restrict__ v,
-                                                       const void *__restrict__ g,
-                                                       uint16_t *__restrict__ out, int64_t n,
-                                                       int64_t ntiles, AdamScalars s,
-                                                       const int32_t *__restrict__ skip)
+// One tile of ROWS x BLOCK 128-bit vectors per workgroup; workgroups are dispatched in
+// tile order, which keeps the set of pages the chip touches at any instant compact.
+// Requires p, m, v 16-byte aligned and g, out aligned to 4 elements.  `tile0` is the
+// tile index of workgroup 0 (launches are cut so that the grid stays below 2^31).
+template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
+__global__ __launch_bounds__(BLOCK) void adam_vec_kernel(float *__restrict__ p, float *__restrict__ m,
+                                                         float *__restrict__ v,
+                                                         const void *__restrict__ g,
+                                                         uint16_t *__restrict__ out, int64_t n,
+                                                         int64_t tile0, AdamScalars s,
+                                                         const int32_t *__restrict__ skip)
 {
-    if (skip && *skip != 0)
-        return;
     const int64_t nvec = n >> 2;
     f32x4 *p4 = reinterpret_cast<f32x4 *>(p);
     f32x4 *m4 = reinterpret_cast<f32x4 *>(m);
     f32x4 *v4 = reinterpret_cast<f32x4 *>(v);
     u32x2 *out2 = reinterpret_cast<u32x2 *>(out);
-    constexpr int64_t kTileVecs = 256 * ROWS;
+    constexpr int64_t kTileVecs = (int64_t)BLOCK * ROWS;
 
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t first = tile * kTileVecs + threadIdx.x;
-        if ((tile + 1) * kTileVecs <= nvec)
-            adam_tile<ROWS, G_BF16, NT, ARITH, false>(p4, m4, v4, g, out2, first, nvec, s);
-        else
-            adam_tile<ROWS, G_BF16, NT, ARITH, true>(p4, m4, v4, g, out2, first, nvec, s);
-    }
+    const int64_t tile = tile0 + blockIdx.x;
+    const int64_t first = tile * kTileVecs + threadIdx.x;
+    if ((tile + 1) * kTileVecs <= nvec)
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false>(p4, m4, v4, g, out2, first, nvec, s, skip);
+    else
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true>(p4, m4, v4, g, out2, first, nvec, s, skip);
 
-    // The last n % 4 elements, one lane each.
+    // The last n % 4 elements, one lane each, in the very first workgroup.
     const int64_t i = (nvec << 2) + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x < 4 && i < n) {
+    if (tile == 0 && threadIdx.x < 4 && i < n && !(skip && *skip != 0)) {
         float pe = p[i], me = m[i], ve = v[i];
         float ge;
         if constexpr (G_BF16)
@@ -246,50 +255,54 @@ __global__ __launch_bounds__(256) void adam_scalar_kernel(float *__restrict__ p,
     }
 }
 
-template <int ROWS, bool G_BF16, bool NT, int ARITH>
-static void launch_vec(dim3 grid, hipStream_t stream, float *p, float *m, float *v, const void *g,
-                       uint16_t *out, int64_t n, int64_t ntiles, const AdamScalars &s,
-                       const int32_t *skip)
+struct VecLaunch {
+    dim3 grid;
+    size_t lds;
+    hipStream_t stream;
+    float *p, *m, *v;
+    const void *g;
+    uint16_t *out;
+    int64_t n, tile0;
+    AdamScalars s;
+    const int32_t *skip;
+};
+
+template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
+static void launch_vec(const VecLaunch &a)
 {
-    hipLaunchKernelGGL((adam_vec_kernel<ROWS, G_BF16, NT, ARITH>), grid, dim3(256), 0, stream, p, m, v,
-                       g, out, n, ntiles, s, skip);
+    hipLaunchKernelGGL((adam_vec_kernel<ROWS, BLOCK, G_BF16, NT, ARITH>), a.grid, dim3(BLOCK), a.lds,
+                       a.stream, a.p, a.m, a.v, a.g, a.out, a.n, a.tile0, a.s, a.skip);
 }
 
-template <int ROWS, bool G_BF16, bool NT>
-static void pick_arith(int arith, dim3 grid, hipStream_t stream, float *p, float *m, float *v,
-                       const void *g, uint16_t *out, int64_t n, int64_t ntiles, const AdamScalars &s,
-                       const int32_t *skip)
+template <int ROWS, int BLOCK, bool G_BF16, bool NT>
+static void pick_arith(int arith, const VecLaunch &a)
 {
     if (arith == 0)
-        launch_vec<ROWS, G_BF16, NT, 0>(grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+        launch_vec<ROWS, BLOCK, G_BF16, NT, 0>(a);
     else if (arith == 1)
-        launch_vec<ROWS, G_BF16, NT, 1>(grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+        launch_vec<ROWS, BLOCK, G_BF16, NT, 1>(a);
     else
-        launch_vec<ROWS, G_BF16, NT, 2>(grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+        launch_vec<ROWS, BLOCK, G_BF16, NT, 2>(a);
 }
 
-template <int ROWS, bool G_BF16>
-static void pick_nt(bool nt, int arith, dim3 grid, hipStream_t stream, float *p, float *m, float *v,
-                    const void *g, uint16_t *out, int64_t n, int64_t ntiles, const AdamScalars &s,
-                    const int32_t *skip)
+template <int ROWS, int BLOCK>
+static void pick_flags(bool g_bf16, bool nt, int arith, const VecLaunch &a)
 {
-    if (nt)
-        pick_arith<ROWS, G_BF16, true>(arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
-    else
-        pick_arith<ROWS, G_BF16, false>(arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    if (g_bf16) {
+        if (nt) pick_arith<ROWS, BLOCK, true, true>(arith, a);
+        else pick_arith<ROWS, BLOCK, true, false>(arith, a);
+    } else {
+        if (nt) pick_arith<ROWS, BLOCK, false, true>(arith, a);
+        else pick_arith<ROWS, BLOCK, false, false>(arith, a);
+    }
 }
 
-template <bool G_BF16>
-static void pick_rows(int rows, bool nt, int arith, dim3 grid, hipStream_t stream, float *p, float *m,
-                      float *v, const void *g, uint16_t *out, int64_t n, int64_t ntiles,
-                      const AdamScalars &s, const int32_t *skip)
+template <int BLOCK>
+static void pick_rows(int rows, bool g_bf16, bool nt, int arith, const VecLaunch &a)
 {
-    if (rows == 1)
-        pick_nt<1, G_BF16>(nt, arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
-    else if (rows == 2)
-        pick_nt<2, G_BF16>(nt, arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
-    else
-        pick_nt<4, G_BF16>(nt, arith, grid, stream, p, m, v, g, out, n, ntiles, s, skip);
+    if (rows == 1) pick_flags<1, BLOCK>(g_bf16, nt, arith, a);
+    else if (rows == 2) pick_flags<2, BLOCK>(g_bf16, nt, arith, a);
+    else pick_flags<4, BLOCK>(g_bf16, nt, arith, a);
 }
 
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
@@ -300,8 +313,6 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
         return ZC_OK;
     const AdamScalars s = make_scalars(hp);
     const Tune &t = tune();
-    int cus = 0;
-    ZC_TRY(num_cus(&cus));
     const bool g_bf16 = g_dtype == ZC_BF16;
     const uintptr_t g_align = g_bf16 ? 8 : 16;
     const bool vec_ok = aligned_to(p, 16) && aligned_to(m, 16) && aligned_to(v, 16) &&
@@ -309,23 +320,27 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
     const int arith = (int)t.adam_arith;
 
     if (vec_ok) {
-        const int rows = (int)t.adam_rows;
-        const int64_t tile_vecs = 256 * (int64_t)rows;
+        const int rows = (int)t.adam_rows, block = (int)t.adam_block;
+        const int64_t tile_vecs = (int64_t)block * rows;
         const int64_t nvec = n >> 2;
         int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
-        int64_t blocks = ntiles > 0 ? ntiles : 1;  // block 0 also owns the n % 4 tail
-        if (t.adam_blocks_per_cu > 0 && blocks > t.adam_blocks_per_cu * cus)
-            blocks = t.adam_blocks_per_cu * cus;
-        if (blocks > 0x7FFFFFFF)
-            blocks = 0x7FFFFFFF;  // the tile loop strides, so any grid covers every tile
-        const dim3 grid((unsigned)blocks);
-        if (g_bf16)
-            pick_rows<true>(rows, t.adam_nontemporal != 0, arith, grid, stream, p, m, v, g, bf16_out, n,
-                            ntiles, s, skip_flag);
-        else
-            pick_rows<false>(rows, t.adam_nontemporal != 0, arith, grid, stream, p, m, v, g, bf16_out, n,
-                             ntiles, s, skip_flag);
+        if (ntiles == 0)
+            ntiles = 1;  // workgroup 0 also owns the n % 4 tail
+        size_t lds = 0;
+        ZC_TRY(occupancy_cap_lds((int)t.adam_waves_per_cu, block, &lds));
+        VecLaunch a{dim3(1), lds, stream, p, m, v, g, bf16_out, n, 0, s, skip_flag};
+        const int64_t kMaxGrid = int64_t(1) << 30;
+        for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
+            const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
+            a.grid = dim3((unsigned)count);
+            a.tile0 = tile0;
+            if (block == 64) pick_rows<64>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
+            else if (block == 128) pick_rows<128>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
+            else pick_rows<256>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
+        }
     } else {
+        int cus = 0;
+        ZC_TRY(num_cus(&cus));
         int64_t blocks = (n + 255) / 256;
         const int64_t cap = (int64_t)cus * 32;
         if (blocks > cap)

@@ -2,7 +2,10 @@
 //
 // Both are pure streaming kernels (6 and 4 bytes per element, no reuse), built
 // on 128-bit accesses with a wave touching contiguous 1 KiB (fp32 / bf16 body)
-// per instruction.
+// per instruction.  Workgroups are single waves that each own one small tile and
+// are dispatched in tile order; the number of resident waves per CU is capped
+// (unused dynamic LDS) because on MI355X a mixed read/write stream loses
+// bandwidth when too many DRAM pages are open at once.
 #include <new>
 #include <vector>
 
@@ -41,39 +44,41 @@ __device__ __forceinline__ uint32_t cast_rne(float x)
     return (u & 0x7FFFFFFFu) > 0x7F800000u ? quiet : rounded;
 }
 
-constexpr int kCastRows = 4;  // 4 x 1024 elements per workgroup tile
+constexpr int kCopyBlock = 64;  // one wave per workgroup: finest dispatch granularity
+constexpr int kCastRows = 4;    // 4 x 256 elements per workgroup tile
+constexpr int64_t kMaxGrid = int64_t(1) << 30;
 
-// Requires src 16-byte and dst 8-byte aligned.
+// Requires src 16-byte and dst 8-byte aligned.  One tile per workgroup; `tile0`
+// is the tile of workgroup 0 (launches are cut to keep the grid below 2^31).
 template <bool NT>
-__global__ __launch_bounds__(256) void cast_vec_kernel(const float *__restrict__ src,
-                                                       uint16_t *__restrict__ dst, int64_t n,
-                                                       int64_t ntiles)
+__global__ __launch_bounds__(kCopyBlock) void cast_vec_kernel(const float *__restrict__ src,
+                                                              uint16_t *__restrict__ dst, int64_t n,
+                                                              int64_t tile0)
 {
     const int64_t nvec = n >> 2;
     const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src);
     u32x2 *d2 = reinterpret_cast<u32x2 *>(dst);
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t first = tile * (256 * kCastRows) + threadIdx.x;
-        f32x4 x[kCastRows];
+    const int64_t tile = tile0 + blockIdx.x;
+    const int64_t first = tile * (kCopyBlock * kCastRows) + threadIdx.x;
+    f32x4 x[kCastRows];
 #pragma unroll
-        for (int r = 0; r < kCastRows; ++r) {
-            const int64_t i = first + r * 256;
-            if (i < nvec)
-                x[r] = ldc<NT>(s4 + i);
-        }
+    for (int r = 0; r < kCastRows; ++r) {
+        const int64_t i = first + r * kCopyBlock;
+        if (i < nvec)
+            x[r] = ldc<NT>(s4 + i);
+    }
 #pragma unroll
-        for (int r = 0; r < kCastRows; ++r) {
-            const int64_t i = first + r * 256;
-            if (i < nvec) {
-                u32x2 w;
-                w.x = cast_rne(x[r].x) | (cast_rne(x[r].y) << 16);
-                w.y = cast_rne(x[r].z) | (cast_rne(x[r].w) << 16);
-                stc<NT>(d2 + i, w);
-            }
+    for (int r = 0; r < kCastRows; ++r) {
+        const int64_t i = first + r * kCopyBlock;
+        if (i < nvec) {
+            u32x2 w;
+            w.x = cast_rne(x[r].x) | (cast_rne(x[r].y) << 16);
+            w.y = cast_rne(x[r].z) | (cast_rne(x[r].w) << 16);
+            stc<NT>(d2 + i, w);
         }
     }
     const int64_t i = (nvec << 2) + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x < 4 && i < n)
+    if (tile == 0 && threadIdx.x < 4 && i < n)
         dst[i] = (uint16_t)cast_rne(src[i]);
 }
 
@@ -92,8 +97,8 @@ __global__ __launch_bounds__(256) void cast_scalar_kernel(const float *__restric
 // search over the prefix sum of tiles per segment.
 // ---------------------------------------------------------------------------
 
-constexpr int64_t kTileVecs = 1024;  // 16 KiB per tile
-constexpr int kUnroll = 4;           // kTileVecs / 256 threads
+constexpr int64_t kTileVecs = 256;  // 4 KiB per tile
+constexpr int kUnroll = 4;          // kTileVecs / kCopyBlock threads
 
 struct SegDesc {
     int64_t src_offset;
@@ -124,15 +129,25 @@ __device__ __forceinline__ u32x4 load_src_vec(const uint16_t *s, unsigned align_
     return w;
 }
 
+constexpr int kHintShift = 10;  // one hint per 1024 tiles
+
+// `hint[k]` is the segment that owns tile k << kHintShift, so the search for a
+// tile's segment starts in a range that is almost always a single segment: one
+// dependent load instead of log2(nsegs) of them before the wave can issue its copy.
 template <bool NT>
-__global__ __launch_bounds__(256) void unshard_kernel(const uint16_t *__restrict__ gathered,
-                                                      const SegDesc *__restrict__ segs,
-                                                      int64_t nsegs, int64_t ntiles)
+__global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const uint16_t *__restrict__ gathered,
+                                                             const SegDesc *__restrict__ segs,
+                                                             const int32_t *__restrict__ hint,
+                                                             int64_t nsegs, int64_t tile0)
 {
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int64_t tile = tile0 + blockIdx.x;
+    {
         // Largest s with segs[s].first_tile <= tile (empty segments share their
         // successor's first_tile and are skipped by taking the last match).
-        int64_t lo = 0, hi = nsegs;
+        const int64_t grp = tile >> kHintShift;
+        int64_t lo = hint[grp], hi = (int64_t)hint[grp + 1] + 1;
+        if (hi > nsegs)
+            hi = nsegs;
         while (hi - lo > 1) {
             const int64_t mid = (lo + hi) >> 1;
             if (segs[mid].first_tile <= tile)
@@ -169,13 +184,13 @@ __global__ __launch_bounds__(256) void unshard_kernel(const uint16_t *__restrict
         u32x4 w[kUnroll];
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) {
-            const int64_t i = first + k * 256;
+            const int64_t i = first + k * kCopyBlock;
             if (i < body_vecs)
                 w[k] = load_src_vec(sb + (i << 3), align_class, NT);
         }
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) {
-            const int64_t i = first + k * 256;
+            const int64_t i = first + k * kCopyBlock;
             if (i < body_vecs)
                 stc<NT>(db + i, w[k]);
         }
@@ -186,6 +201,7 @@ __global__ __launch_bounds__(256) void unshard_kernel(const uint16_t *__restrict
 
 struct zc_unshard_plan {
     zc::SegDesc *segs_dev = nullptr;
+    int32_t *hint_dev = nullptr;
     int64_t nsegs = 0;
     int64_t ntiles = 0;
     int64_t gathered_numel = 0;
@@ -218,19 +234,21 @@ zc_status zc_cast_bf16(const float *src, uint16_t *dst, int64_t n, void *hip_str
     const Tune &t = tune();
     if (aligned_to(src, 16) && aligned_to(dst, 8)) {
         const int64_t nvec = n >> 2;
-        const int64_t tile_vecs = 256 * kCastRows;
-        const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
-        int64_t blocks = ntiles > 0 ? ntiles : 1;
-        if (t.copy_blocks_per_cu > 0 && blocks > t.copy_blocks_per_cu * cus)
-            blocks = t.copy_blocks_per_cu * cus;
-        if (blocks > 0x7FFFFFFF)
-            blocks = 0x7FFFFFFF;
-        if (t.copy_nontemporal)
-            hipLaunchKernelGGL(cast_vec_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, src,
-                               dst, n, ntiles);
-        else
-            hipLaunchKernelGGL(cast_vec_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src,
-                               dst, n, ntiles);
+        const int64_t tile_vecs = kCopyBlock * kCastRows;
+        int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+        if (ntiles == 0)
+            ntiles = 1;  // workgroup 0 also owns the n % 4 tail
+        size_t lds = 0;
+        ZC_TRY(occupancy_cap_lds((int)t.cast_waves_per_cu, kCopyBlock, &lds));
+        for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
+            const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
+            if (t.copy_nontemporal)
+                hipLaunchKernelGGL(cast_vec_kernel<true>, dim3((unsigned)count), dim3(kCopyBlock), lds,
+                                   stream, src, dst, n, tile0);
+            else
+                hipLaunchKernelGGL(cast_vec_kernel<false>, dim3((unsigned)count), dim3(kCopyBlock), lds,
+                                   stream, src, dst, n, tile0);
+        }
     } else {
         int64_t blocks = (n + 255) / 256;
         if (blocks > (int64_t)cus * 32)
@@ -290,6 +308,26 @@ zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t 
         table.push_back(d);
     }
 
+    if (nsegs > 0x7FFFFFFF)
+        return fail(ZC_ERR_UNSUPPORTED, "more than 2^31 segments");
+    // hint[k] = last segment whose first tile is <= k << kHintShift, for k = 0 .. groups
+    const int64_t groups = (ntiles >> kHintShift) + 1;
+    std::vector<int32_t> hints;
+    try {
+        hints.resize((size_t)groups + 1);
+    } catch (const std::bad_alloc &) {
+        return fail(ZC_ERR_NOMEM, "cannot allocate the host hint table");
+    }
+    {
+        int64_t seg = 0;
+        for (int64_t k = 0; k <= groups; ++k) {
+            const int64_t tile = k << kHintShift;
+            while (seg + 1 < nsegs && table[(size_t)seg + 1].first_tile <= tile)
+                ++seg;
+            hints[(size_t)k] = (int32_t)seg;
+        }
+    }
+
     zc_unshard_plan *plan = new (std::nothrow) zc_unshard_plan;
     if (!plan)
         return fail(ZC_ERR_NOMEM, "cannot allocate the plan");
@@ -302,8 +340,15 @@ zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t 
         if (e == hipSuccess)
             e = hipMemcpy(plan->segs_dev, table.data(), sizeof(SegDesc) * (size_t)nsegs,
                           hipMemcpyHostToDevice);
+        if (e == hipSuccess)
+            e = hipMalloc(reinterpret_cast<void **>(&plan->hint_dev), sizeof(int32_t) * hints.size());
+        if (e == hipSuccess)
+            e = hipMemcpy(plan->hint_dev, hints.data(), sizeof(int32_t) * hints.size(),
+                          hipMemcpyHostToDevice);
     }
     if (e != hipSuccess) {
+        if (plan->hint_dev)
+            (void)hipFree(plan->hint_dev);
         if (plan->segs_dev)
             (void)hipFree(plan->segs_dev);
         delete plan;
@@ -329,21 +374,20 @@ zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void
     if (dev != plan->device)
         return fail(ZC_ERR_INVALID_ARG, "plan was created on device %d, current device is %d",
                     plan->device, dev);
-    int cus = 0;
-    ZC_TRY(num_cus(&cus));
     const Tune &t = tune();
-    int64_t blocks = plan->ntiles;
-    if (t.copy_blocks_per_cu > 0 && blocks > t.copy_blocks_per_cu * cus)
-        blocks = t.copy_blocks_per_cu * cus;
-    if (blocks > 0x7FFFFFFF)
-        blocks = 0x7FFFFFFF;
+    size_t lds = 0;
+    ZC_TRY(occupancy_cap_lds((int)t.copy_waves_per_cu, kCopyBlock, &lds));
     hipStream_t stream = (hipStream_t)hip_stream;
-    if (t.copy_nontemporal)
-        hipLaunchKernelGGL(unshard_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, gathered,
-                           plan->segs_dev, plan->nsegs, plan->ntiles);
-    else
-        hipLaunchKernelGGL(unshard_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, gathered,
-                           plan->segs_dev, plan->nsegs, plan->ntiles);
+    for (int64_t tile0 = 0; tile0 < plan->ntiles; tile0 += kMaxGrid) {
+        const int64_t left = plan->ntiles - tile0;
+        const int64_t count = left < kMaxGrid ? left : kMaxGrid;
+        if (t.copy_nontemporal)
+            hipLaunchKernelGGL(unshard_kernel<true>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
+                               gathered, plan->segs_dev, plan->hint_dev, plan->nsegs, tile0);
+        else
+            hipLaunchKernelGGL(unshard_kernel<false>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
+                               gathered, plan->segs_dev, plan->hint_dev, plan->nsegs, tile0);
+    }
     ZC_HIP(hipGetLastError());
     return ZC_OK;
 }
@@ -354,8 +398,13 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan)
     if (!plan)
         return ZC_OK;
     hipError_t e = hipSuccess;
-    if (plan->segs_dev)
-        e = hipFree(plan->segs_dev);
+    if (plan->hint_dev)
+        e = hipFree(plan->hint_dev);
+    if (plan->segs_dev) {
+        const hipError_t e2 = hipFree(plan->segs_dev);
+        if (e == hipSuccess)
+            e = e2;
+    }
     delete plan;
     if (e != hipSuccess)
         return hip_fail(e, "hipFree(descriptor table)");

@@ -53,6 +53,40 @@ zc_status num_cus(int *out)
     return ZC_OK;
 }
 
+zc_status occupancy_cap_lds(int waves_per_cu, int block_threads, size_t *lds_bytes)
+{
+    *lds_bytes = 0;
+    if (waves_per_cu <= 0)
+        return ZC_OK;
+    static std::mutex mu;
+    static int lds_per_cu[64];
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return fail(ZC_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (lds_per_cu[dev] == 0) {
+            int bytes = 0;
+            ZC_HIP(hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev));
+            if (bytes <= 0)
+                bytes = 64 * 1024;
+            lds_per_cu[dev] = bytes;
+        }
+    }
+    const int waves_per_block = (block_threads + 63) / 64;
+    int blocks = waves_per_cu / waves_per_block;
+    if (blocks < 1)
+        blocks = 1;
+    // Largest request that still lets `blocks` workgroups share one CU's LDS.
+    size_t bytes = (size_t)lds_per_cu[dev] / (size_t)blocks;
+    bytes &= ~(size_t)255;
+    if (bytes > 64 * 1024)
+        bytes = 64 * 1024;  // default per-workgroup limit for dynamic LDS
+    *lds_bytes = bytes;
+    return ZC_OK;
+}
+
 zc_status check_dtype(zc_dtype t)
 {
     if (t != ZC_F32 && t != ZC_BF16)
@@ -93,10 +127,12 @@ struct Knob {
 
 static const Knob kKnobs[] = {
     {"adam.rows", &Tune::adam_rows, 1, 4},
-    {"adam.blocks_per_cu", &Tune::adam_blocks_per_cu, 0, 64},
+    {"adam.block", &Tune::adam_block, 64, 256},
+    {"adam.waves_per_cu", &Tune::adam_waves_per_cu, 0, 64},
     {"adam.nontemporal", &Tune::adam_nontemporal, 0, 1},
     {"adam.arith", &Tune::adam_arith, 0, 2},
-    {"copy.blocks_per_cu", &Tune::copy_blocks_per_cu, 0, 64},
+    {"copy.waves_per_cu", &Tune::copy_waves_per_cu, 0, 64},
+    {"cast.waves_per_cu", &Tune::cast_waves_per_cu, 0, 64},
     {"copy.nontemporal", &Tune::copy_nontemporal, 0, 1},
     {"offload.zero_copy", &Tune::offload_zero_copy, 0, 1},
 };
@@ -124,7 +160,9 @@ zc_status zc_tune_set(const char *key, int64_t value)
     const zc::Knob *k = zc::find_knob(key);
     if (!k)
         return zc::fail(ZC_ERR_INVALID_ARG, "unknown tuning key '%s'", key ? key : "(null)");
-    if (value < k->lo || value > k->hi || (k->field == &zc::Tune::adam_rows && value == 3))
+    const bool pow2 = value > 0 && (value & (value - 1)) == 0;
+    if (value < k->lo || value > k->hi ||
+        ((k->field == &zc::Tune::adam_rows || k->field == &zc::Tune::adam_block) && !pow2))
         return zc::fail(ZC_ERR_INVALID_ARG, "value %lld out of range for '%s'", (long long)value, key);
     zc::tune().*(k->field) = value;
     return ZC_OK;

@@ -29,17 +29,24 @@ void clear_error();
 
 struct Tune {
     int64_t adam_rows = 2;
-    int64_t adam_blocks_per_cu = 0;
-    int64_t adam_nontemporal = 0;
-    int64_t adam_arith = 1;
-    int64_t copy_blocks_per_cu = 0;
-    int64_t copy_nontemporal = 0;
+    int64_t adam_block = 128;
+    int64_t adam_waves_per_cu = 12;
+    int64_t adam_nontemporal = 1;
+    int64_t adam_arith = 2;
+    int64_t copy_waves_per_cu = 16;
+    int64_t cast_waves_per_cu = 24;
+    int64_t copy_nontemporal = 1;
     int64_t offload_zero_copy = 0;
 };
 Tune &tune();
 
 // Compute units of the current device (cached per device ordinal).
 zc_status num_cus(int *out);
+
+// Dynamic-LDS request (bytes, never touched by the kernel) that limits a kernel
+// with `block_threads` threads per workgroup to about `waves_per_cu` resident
+// waves per compute unit; 0 waves means no cap (0 bytes).
+zc_status occupancy_cap_lds(int waves_per_cu, int block_threads, size_t *lds_bytes);
 
 // Host-side validation shared by the resident and the offloaded step.
 zc_status check_hparams(const zc_adam_hparams *hp);

@@ -13,6 +13,7 @@
 //
 // Both copy directions run concurrently on separate DMA queues, so a full-duplex
 // host link is busy both ways while the (much shorter) kernel hides in between.
+#include <chrono>
 #include <new>
 
 #include "zc_internal.h"
@@ -118,6 +119,56 @@ zc_status zc_offload_create(int64_t chunk_bytes, int32_t num_buffers, zc_offload
 zc_status zc_offload_destroy(zc_offload_ctx *ctx)
 {
     zc::destroy_ctx(ctx);
+    return ZC_OK;
+}
+
+zc_status zc_offload_probe_link(zc_offload_ctx *ctx, const void *host_src, void *host_dst, int64_t bytes,
+                                int32_t mode, float *ms_out)
+{
+    using namespace zc;
+    if (!ctx || !ms_out)
+        return fail(ZC_ERR_INVALID_ARG, "ctx / ms_out is NULL");
+    if (bytes <= 0 || mode < 0 || mode > 2)
+        return fail(ZC_ERR_INVALID_ARG, "need bytes > 0 and mode in {0, 1, 2}");
+    const bool do_h2d = mode == 0 || mode == 2, do_d2h = mode == 1 || mode == 2;
+    if (do_h2d) {
+        if (!host_src)
+            return fail(ZC_ERR_INVALID_ARG, "host_src is NULL");
+        ZC_TRY(require_pinned(host_src, "host_src"));
+    }
+    if (do_d2h) {
+        if (!host_dst)
+            return fail(ZC_ERR_INVALID_ARG, "host_dst is NULL");
+        ZC_TRY(require_pinned(host_dst, "host_dst"));
+    }
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev != ctx->device)
+        return fail(ZC_ERR_INVALID_ARG, "context belongs to device %d", ctx->device);
+    // The staging ring is only a landing zone here: slots are reused without fences
+    // because nobody reads what the probe copies.
+    const int64_t cb = ctx->chunk_bytes;
+    const int64_t slots = (int64_t)ctx->num_buffers * 3;
+    char *stage = reinterpret_cast<char *>(ctx->staging);
+    ZC_HIP(hipStreamSynchronize(ctx->h2d));
+    ZC_HIP(hipStreamSynchronize(ctx->d2h));
+    const auto t0 = std::chrono::steady_clock::now();
+    int64_t k = 0;
+    for (int64_t off = 0; off < bytes; off += cb, ++k) {
+        const size_t cnt = (size_t)((bytes - off) < cb ? (bytes - off) : cb);
+        // the two directions use different halves of the ring where it has room for both
+        const int64_t up = k % slots, down = (k + slots / 2) % slots;
+        if (do_h2d)
+            ZC_HIP(hipMemcpyAsync(stage + up * cb, static_cast<const char *>(host_src) + off, cnt,
+                                  hipMemcpyHostToDevice, ctx->h2d));
+        if (do_d2h)
+            ZC_HIP(hipMemcpyAsync(static_cast<char *>(host_dst) + off, stage + down * cb, cnt,
+                                  hipMemcpyDeviceToHost, ctx->d2h));
+    }
+    ZC_HIP(hipStreamSynchronize(ctx->h2d));
+    ZC_HIP(hipStreamSynchronize(ctx->d2h));
+    const auto t1 = std::chrono::steady_clock::now();
+    *ms_out = std::chrono::duration<float, std::milli>(t1 - t0).count();
     return ZC_OK;
 }
 

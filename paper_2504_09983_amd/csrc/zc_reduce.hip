@@ -59,7 +59,10 @@ __device__ __forceinline__ void block_fold(double sum, uint32_t bad, Partial *ou
     }
 }
 
-// bf16 input, 8 elements (16 bytes) per lane per row.  Requires 16-byte alignment.
+constexpr int kReduceUnroll = 4;  // 128-bit loads in flight per lane
+
+// bf16 input, 8 elements (16 bytes) per lane per load, kReduceUnroll loads issued
+// back to back.  Requires 16-byte alignment.
 __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__restrict__ g, int64_t n,
                                                           Partial *__restrict__ partials)
 {
@@ -67,27 +70,37 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
     const u32x4 *g4 = reinterpret_cast<const u32x4 *>(g);
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     uint32_t worst = 0;  // running max of |bits| per half-word; >= 0x7F80 means Inf/NaN
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
-        const u32x4 w = g4[i];
-        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
-        float lo[4], hi[4];
+    const int64_t tile_vecs = 256 * kReduceUnroll;
+    const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t first = tile * tile_vecs + threadIdx.x;
+        u32x4 w[kReduceUnroll];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            lo[k] = __uint_as_float(ws[k] << 16);
-            hi[k] = __uint_as_float(ws[k] & 0xFFFF0000u);
-            const uint32_t mag_lo = ws[k] & 0x7FFFu;
-            const uint32_t mag_hi = (ws[k] >> 16) & 0x7FFFu;
-            worst = max(worst, max(mag_lo, mag_hi));
+        for (int u = 0; u < kReduceUnroll; ++u) {
+            const int64_t i = first + u * 256;
+            w[u] = i < nvec ? __builtin_nontemporal_load(g4 + i) : u32x4{0u, 0u, 0u, 0u};
         }
-        a0 = fmaf(lo[0], lo[0], a0);
-        a1 = fmaf(hi[0], hi[0], a1);
-        a2 = fmaf(lo[1], lo[1], a2);
-        a3 = fmaf(hi[1], hi[1], a3);
-        a0 = fmaf(lo[2], lo[2], a0);
-        a1 = fmaf(hi[2], hi[2], a1);
-        a2 = fmaf(lo[3], lo[3], a2);
-        a3 = fmaf(hi[3], hi[3], a3);
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u) {
+            const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+            float lo[4], hi[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                lo[k] = __uint_as_float(ws[k] << 16);
+                hi[k] = __uint_as_float(ws[k] & 0xFFFF0000u);
+                const uint32_t mag_lo = ws[k] & 0x7FFFu;
+                const uint32_t mag_hi = (ws[k] >> 16) & 0x7FFFu;
+                worst = max(worst, max(mag_lo, mag_hi));
+            }
+            a0 = fmaf(lo[0], lo[0], a0);
+            a1 = fmaf(hi[0], hi[0], a1);
+            a2 = fmaf(lo[1], lo[1], a2);
+            a3 = fmaf(hi[1], hi[1], a3);
+            a0 = fmaf(lo[2], lo[2], a0);
+            a1 = fmaf(hi[2], hi[2], a1);
+            a2 = fmaf(lo[3], lo[3], a2);
+            a3 = fmaf(hi[3], hi[3], a3);
+        }
     }
     double sum = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     // The last n % 8 elements, one lane each, in workgroup 0.
@@ -101,7 +114,7 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
     block_fold(sum, worst >= 0x7F80u ? 1u : 0u, partials + blockIdx.x);
 }
 
-// fp32 input, 4 elements per lane per row.  Requires 16-byte alignment.
+// fp32 input, 4 elements per lane per load.  Requires 16-byte alignment.
 __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict__ g, int64_t n,
                                                          Partial *__restrict__ partials)
 {
@@ -109,16 +122,27 @@ __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict
     const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     uint32_t worst = 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
-        const f32x4 x = g4[i];
-        a0 = fmaf(x.x, x.x, a0);
-        a1 = fmaf(x.y, x.y, a1);
-        a2 = fmaf(x.z, x.z, a2);
-        a3 = fmaf(x.w, x.w, a3);
-        worst = max(max(worst, __float_as_uint(x.x) & 0x7FFFFFFFu),
-                    max(__float_as_uint(x.y) & 0x7FFFFFFFu,
-                        max(__float_as_uint(x.z) & 0x7FFFFFFFu, __float_as_uint(x.w) & 0x7FFFFFFFu)));
+    const int64_t tile_vecs = 256 * kReduceUnroll;
+    const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t first = tile * tile_vecs + threadIdx.x;
+        f32x4 x[kReduceUnroll];
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u) {
+            const int64_t i = first + u * 256;
+            x[u] = i < nvec ? __builtin_nontemporal_load(g4 + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u) {
+            a0 = fmaf(x[u].x, x[u].x, a0);
+            a1 = fmaf(x[u].y, x[u].y, a1);
+            a2 = fmaf(x[u].z, x[u].z, a2);
+            a3 = fmaf(x[u].w, x[u].w, a3);
+            worst = max(max(worst, __float_as_uint(x[u].x) & 0x7FFFFFFFu),
+                        max(__float_as_uint(x[u].y) & 0x7FFFFFFFu,
+                            max(__float_as_uint(x[u].z) & 0x7FFFFFFFu,
+                                __float_as_uint(x[u].w) & 0x7FFFFFFFu)));
+        }
     }
     double sum = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     const int64_t t = (nvec << 2) + threadIdx.x;
@@ -221,7 +245,7 @@ extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, 
 
     int blocks = 0;
     if (n > 0) {
-        const int64_t per_lane = bf16 ? 8 : 4;
+        const int64_t per_lane = (bf16 ? 8 : 4) * kReduceUnroll;
         const int64_t want = (n / per_lane + 255) / 256;
         int64_t cap = (int64_t)cus * 8;
         if (cap > kMaxPartials)

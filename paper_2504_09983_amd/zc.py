@@ -84,6 +84,8 @@ def lib():
                                        ctypes.POINTER(AdamHparams), vp, vp, vp]
     L.zc_offload_destroy.restype = ctypes.c_int
     L.zc_offload_destroy.argtypes = [vp]
+    L.zc_offload_probe_link.restype = ctypes.c_int
+    L.zc_offload_probe_link.argtypes = [vp, vp, vp, i64, i32, ctypes.POINTER(ctypes.c_float)]
     L.zc_grad_sqnorm.restype = ctypes.c_int
     L.zc_grad_sqnorm.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp]
     L.zc_tune_set.restype = ctypes.c_int
@@ -206,6 +208,13 @@ class OffloadCtx:
                                           n_resident, _addr(p_host), _addr(m_host), _addr(v_host),
                                           n_streamed, _addr(g_dev), g_dtype, ctypes.byref(hp),
                                           _addr(bf16_out_dev), _addr(skip_flag), _stream(stream)))
+
+    def probe_link(self, host_src, host_dst, nbytes: int, mode: int) -> float:
+        """Wall milliseconds of plain chunked pinned copies (0 = H2D, 1 = D2H, 2 = both)."""
+        ms = ctypes.c_float(0.0)
+        _check(lib().zc_offload_probe_link(self._h, _addr(host_src), _addr(host_dst), nbytes, mode,
+                                           ctypes.byref(ms)))
+        return ms.value
 
     def destroy(self) -> None:
         if self._h is not None and self._h.value is not None:

@@ -108,18 +108,18 @@ def test_misaligned_pointers(offset, g_bf16):
 @pytest.mark.parametrize("arith", [0, 1, 2])
 @pytest.mark.parametrize("rows", [1, 2, 4])
 def test_every_kernel_variant(arith, rows):
-    old = {k: zc.tune_get(k) for k in ("adam.arith", "adam.rows", "adam.nontemporal",
-                                       "adam.blocks_per_cu")}
+    keys = ("adam.arith", "adam.rows", "adam.nontemporal", "adam.block", "adam.waves_per_cu")
+    old = {k: zc.tune_get(k) for k in keys}
     try:
         for nt in (0, 1):
-            for bpc in (0, 2):
-                zc.tune_set("adam.arith", arith); zc.tune_set("adam.rows", rows)
-                zc.tune_set("adam.nontemporal", nt); zc.tune_set("adam.blocks_per_cu", bpc)
-                n = 256 * 1024 * 3 + 1029   # several tiles per workgroup in persistent mode
+            for block, waves in ((64, 9), (128, 0), (256, 12)):
+                for k, val in zip(keys, (arith, rows, nt, block, waves)):
+                    zc.tune_set(k, val)
+                n = 256 * 1024 * 3 + 1029
                 for g_bf16 in (False, True):
                     gpu, cpu = run_both(n, 2, g_bf16=g_bf16, seed=7)
-                    check(gpu, cpu, tag=f"arith={arith} rows={rows} nt={nt} bpc={bpc} bf16={g_bf16}",
-                          steps=2)
+                    check(gpu, cpu, steps=2,
+                          tag=f"arith={arith} rows={rows} nt={nt} block={block} bf16={g_bf16}")
     finally:
         for k, val in old.items():
             zc.tune_set(k, val)

@@ -159,10 +159,10 @@ def test_unshard_every_relative_alignment(src_shift):
     run_unshard(numels, align=1, dst_shift=[0, 1, 2, 3, 4, 5, 6, 7], src_shift=src_shift)
 
 
-def test_unshard_persistent_grid_and_nontemporal():
+def test_unshard_occupancy_cap_and_nontemporal():
     numels = [4096 * 64 + 3, 1000, 4096 * 200, 17]
-    for tune in ({"copy.blocks_per_cu": 1}, {"copy.nontemporal": 1},
-                 {"copy.blocks_per_cu": 2, "copy.nontemporal": 1}):
+    for tune in ({"copy.waves_per_cu": 0}, {"copy.nontemporal": 0},
+                 {"copy.waves_per_cu": 4, "copy.nontemporal": 1}):
         run_unshard(numels, tune=tune)
 
 

@@ -107,6 +107,8 @@ def test_tune_knobs():
     assert zc.tune_get("adam.rows") == 4
     assert _status(zc.tune_set, "adam.rows", 3) == zc.ERR_INVALID_ARG
     assert _status(zc.tune_set, "adam.rows", 9) == zc.ERR_INVALID_ARG
+    assert _status(zc.tune_set, "adam.block", 96) == zc.ERR_INVALID_ARG
+    assert _status(zc.tune_set, "adam.block", 512) == zc.ERR_INVALID_ARG
     assert _status(zc.tune_set, "no.such.key", 1) == zc.ERR_INVALID_ARG
     assert _status(zc.tune_get, "no.such.key") == zc.ERR_INVALID_ARG
     zc.tune_set("adam.rows", old)
