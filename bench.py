@@ -41,6 +41,9 @@ def parse_args():
                     choices=["llama3_8b", "llama3_70b", "mixtral_8x7b", "tiny"])
     ap.add_argument("--no-unshard", action="store_true",
                     help="leave the unshard copy out (needed for 70B/Mixtral to fit with the step)")
+    ap.add_argument("--only-unshard", action="store_true",
+                    help="time the unshard copy alone (Mixtral: the step's state and the two "
+                         "93 GB buffers do not fit in HBM together)")
     ap.add_argument("--offload-elems", type=int, default=1 << 28,
                     help="elements streamed in the offload leg (0 = skip the leg)")
     ap.add_argument("--offload-frac", type=float, default=0.0, help="resident fraction f")
@@ -58,6 +61,43 @@ def parse_args():
 
 def gb(x):
     return x / 1e9
+
+
+def bind_to_gpu_numa_node(torch):
+    """Run this process on the CPUs of the NUMA node the GPU hangs off, so that pinned
+    host memory allocated afterwards is local to the GPU's PCIe root (device writes to
+    memory on another socket cross the inter-socket link and run several times slower).
+    Returns a small dict describing what was done."""
+    info = {"gpu_numa_node": None, "bound": False}
+    try:
+        props = torch.cuda.get_device_properties(0)
+        bus = getattr(props, "pci_bus_id", None)
+        dom = getattr(props, "pci_domain_id", 0)
+        dev_id = getattr(props, "pci_device_id", 0)
+        if bus is None:
+            return info
+        path = f"/sys/bus/pci/devices/{dom:04x}:{bus:02x}:{dev_id:02x}.0/numa_node"
+        node = int(open(path).read().strip())
+        info["gpu_numa_node"] = node
+        if node < 0:
+            return info
+        cpus = set()
+        for part in open(f"/sys/devices/system/node/node{node}/cpulist").read().strip().split(","):
+            if "-" in part:
+                a, b = part.split("-")
+                cpus.update(range(int(a), int(b) + 1))
+            elif part:
+                cpus.add(int(part))
+        allowed = os.sched_getaffinity(0)
+        use = cpus & allowed
+        info["allowed_cpus"] = len(allowed)
+        info["node_cpus_allowed"] = len(use)
+        if use:
+            os.sched_setaffinity(0, use)
+            info["bound"] = True
+    except Exception as e:  # best effort: the numbers are still valid, only maybe slower
+        info["error"] = repr(e)
+    return info
 
 
 def main():
@@ -105,12 +145,14 @@ def main():
     do_unshard = not args.no_unshard
     hp_kw = dict(synth.HP)
 
-    p = torch.empty(n, dtype=torch.float32, device=dev)
-    m = torch.zeros(n, dtype=torch.float32, device=dev)
-    v = torch.zeros(n, dtype=torch.float32, device=dev)
-    g = torch.empty(n, dtype=torch.bfloat16, device=dev)
-    synth.device_normal_(p, synth.P_STD, seed=2)
-    synth.device_normal_(g, synth.G_STD, seed=2001)
+    do_step = not args.only_unshard
+    if do_step:
+        p = torch.empty(n, dtype=torch.float32, device=dev)
+        m = torch.zeros(n, dtype=torch.float32, device=dev)
+        v = torch.zeros(n, dtype=torch.float32, device=dev)
+        g = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        synth.device_normal_(p, synth.P_STD, seed=2)
+        synth.device_normal_(g, synth.G_STD, seed=2001)
     norm = torch.zeros(1, dtype=torch.float32, device=dev)
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
     if do_unshard:
@@ -130,9 +172,11 @@ def main():
         step_no[0] += 1
         hp = zc.hparams(step=step_no[0], **hp_kw)
         if ev: ev[0].record()
-        zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
+        if do_step:
+            zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
         if ev: ev[1].record()
-        zc.adam_step(p, m, v, g, zc.BF16, n, hp, bf16_out=send, skip_flag=flag)
+        if do_step:
+            zc.adam_step(p, m, v, g, zc.BF16, n, hp, bf16_out=send, skip_flag=flag)
         if ev: ev[2].record()
         if do_unshard:
             zc.unshard(plan, gathered)
@@ -157,12 +201,12 @@ def main():
     t_norm, t_adam, t_unshard = avg(0), avg(1), avg(2)
     assert flag.item() == 0, "synthetic gradients must be finite"
 
-    kernels = {
-        "sqnorm": dict(name="zc::sqnorm_bf16_kernel", ms=t_norm, bytes=2 * n, units=n,
-                       bytes_per_unit=2),
-        "adam": dict(name="zc::adam_vec_kernel", ms=t_adam, bytes=28 * n, units=n,
-                     bytes_per_unit=28),
-    }
+    kernels = {}
+    if do_step:
+        kernels["sqnorm"] = dict(name="zc::sqnorm_bf16_kernel", ms=t_norm, bytes=2 * n, units=n,
+                                 bytes_per_unit=2)
+        kernels["adam"] = dict(name="zc::adam_vec_kernel", ms=t_adam, bytes=28 * n, units=n,
+                               bytes_per_unit=28)
     if do_unshard:
         kernels["unshard"] = dict(name="zc::unshard_kernel", ms=t_unshard, bytes=4 * total,
                                   units=total, bytes_per_unit=4)
@@ -197,8 +241,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "f32", 1: "f32+f64", 2: "f64"}[zc.tune_get("adam.arith")], "data": "synthetic",
         "config": {
-            "workload": (f"{args.workload} one-of-{WORLD} shard: grad-norm + fused AdamW with bf16 copy"
-                         + (" + unshard of the 8-shard gathered buffer" if do_unshard else "")),
+            "workload": (f"{args.workload} one-of-{WORLD} shard: "
+                         + ("grad-norm + fused AdamW with bf16 copy" if do_step else "")
+                         + (" + " if do_step and do_unshard else "")
+                         + ("unshard of the 8-shard gathered buffer" if do_unshard else "")),
             "shard_elements": n, "model_elements": total, "tensors": len(numels),
             "grads": "bf16", "state": "fp32 p/m/v resident in HBM",
             "tuning": {k: zc.tune_get(k) for k in ("adam.arith", "adam.block", "adam.rows",
@@ -210,25 +256,35 @@ def main():
                             algorithmic_bytes=d["bytes"],
                             rate_G_per_s=round(d["units"] / (d["ms"] * 1e-3) / 1e9, 2))
                     for k, d in kernels.items()},
-        "adam_step_gparams_per_s": round(n / (t_adam * 1e-3) / 1e9, 2),
     }
+    if do_step:
+        result["adam_step_gparams_per_s"] = round(n / (t_adam * 1e-3) / 1e9, 2)
 
     # ---- free the resident workload before the extra legs --------------------------
     if do_unshard:
         plan.destroy()
         del outs, gathered
-    del p, m, v, g, send
+    if do_step:
+        del p, m, v, g
+    del send
     torch.cuda.empty_cache()
 
     if args.offload_elems > 0:
-        result["offload"] = offload_leg(torch, synth, zc, dev, args)
+        legs = {}
+        keep = zc.tune_get("offload.zero_copy")
+        for mode, name in ((1, "zero_copy"), (0, "staged_ring")):
+            zc.tune_set("offload.zero_copy", mode)
+            legs[name] = offload_leg(torch, synth, zc, dev, args, probe=(mode == 0))
+        zc.tune_set("offload.zero_copy", keep)
+        result["offload"] = legs
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_leg(synth)
     print(json.dumps(result))
 
 
-def offload_leg(torch, synth, zc, dev, args):
+def offload_leg(torch, synth, zc, dev, args, probe=True):
     """Offloaded step: p/m/v of the streamed part in pinned host DRAM, 3-slot ring."""
+    numa = bind_to_gpu_numa_node(torch)
     n = int(args.offload_elems)
     n_res = int(args.offload_frac * n) // 1024 * 1024
     n_str = n - n_res
@@ -261,11 +317,16 @@ def offload_leg(torch, synth, zc, dev, args):
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
 
-    # plain pinned-copy ceilings with the same chunking: one direction at a time and both
-    nbytes = 4 * n_str
-    t_h2d = min(ctx.probe_link(hp_, hv_, nbytes, 0) for _ in range(3)) * 1e-3
-    t_d2h = min(ctx.probe_link(hp_, hv_, nbytes, 1) for _ in range(3)) * 1e-3
-    t_both = min(ctx.probe_link(hp_, hv_, nbytes, 2) for _ in range(3)) * 1e-3
+    extra = {}
+    if probe:
+        # plain pinned-copy ceilings with the same chunking: one direction at a time and both
+        nbytes = 4 * n_str
+        t_h2d = min(ctx.probe_link(hp_, hv_, nbytes, 0) for _ in range(3)) * 1e-3
+        t_d2h = min(ctx.probe_link(hp_, hv_, nbytes, 1) for _ in range(3)) * 1e-3
+        t_both = min(ctx.probe_link(hp_, hv_, nbytes, 2) for _ in range(3)) * 1e-3
+        extra["memcpy_ceiling_GBps"] = {"h2d": round(gb(nbytes) / t_h2d, 2),
+                                        "d2h": round(gb(nbytes) / t_d2h, 2),
+                                        "both_each": round(gb(nbytes) / t_both, 2)}
     ctx.destroy()
     one_way = 12 * n_str
     return {
@@ -274,10 +335,8 @@ def offload_leg(torch, synth, zc, dev, args):
         "gparams_per_s": round(n / dt / 1e9, 3),
         "link_GBps_each_direction": round(gb(one_way) / dt, 2),
         "link_peak_GBps": PCIE_PEAK_GBS, "frac_of_link_peak": round(gb(one_way) / dt / PCIE_PEAK_GBS, 4),
-        "memcpy_ceiling_GBps": {"h2d": round(gb(4 * n_str) / t_h2d, 2),
-                                "d2h": round(gb(4 * n_str) / t_d2h, 2),
-                                "both_each": round(gb(4 * n_str) / t_both, 2)},
         "zero_copy": zc.tune_get("offload.zero_copy"),
+        "host_numa": numa, **extra,
     }
 
 

@@ -152,10 +152,17 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  * to host memory and overlaps the copies with computation while the update
  * itself stays on the GPU).  Elements [0, n_resident) of the partition live
  * in DEVICE arrays p_dev/m_dev/v_dev; elements [n_resident, n_resident +
- * n_streamed) live in pinned HOST arrays p_host/m_host/v_host and are streamed
- * host -> staging slot -> kernel -> host in chunks of chunk_bytes per array,
- * with num_buffers staging slots, copies and kernel on separate streams.
- * Results are bit-identical to zc_adam_step over the concatenation.
+ * n_streamed) live in pinned HOST arrays p_host/m_host/v_host and cross the
+ * host link once in each direction.  Two transports, chosen by the knob
+ * "offload.zero_copy" (results are bit-identical to zc_adam_step over the
+ * concatenation either way):
+ *   1 (default)  the update kernel reads and writes the pinned host arrays
+ *                directly through the link; one launch on `hip_stream`, no
+ *                staging memory, no copy engines.
+ *   0            staged ring: host -> staging slot -> kernel -> host in chunks
+ *                of chunk_bytes per array through num_buffers slots, copies on
+ *                two internal streams (hipMemcpyAsync) and the kernel on
+ *                `hip_stream`, fenced by events.
  *
  * zc_offload_create   chunk_bytes: bytes per fp32 array per chunk, a positive
  *                     multiple of 4096 (64 MiB in the reference workload);
@@ -168,6 +175,8 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  *   g_dev             DEVICE, n_resident + n_streamed elements of g_dtype.
  *   bf16_out_dev      DEVICE uint16[n_resident + n_streamed] or NULL.
  *   A context serves one step at a time; concurrent calls on one context race.
+ *   The host arrays must not be touched by the host until `hip_stream` has
+ *   passed the call.
  */
 zc_status zc_offload_create(int64_t chunk_bytes, int32_t num_buffers, zc_offload_ctx **out);
 zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, float *v_dev,
@@ -212,7 +221,11 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
  *                      2 = fp64 throughout
  *   "copy.waves_per_cu", "cast.waves_per_cu"  the same cap for unshard and for the cast
  *   "copy.nontemporal"  non-temporal accesses in cast and unshard
- *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host
+ *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default)
+ *   "offload.zc_waves_per_cu"  resident-wave cap of the zero-copy kernel (0 = none)
+ *   "offload.max_ahead" 1 = the staged ring blocks the host so that it never runs more
+ *                      than num_buffers chunks ahead of finished copy-backs
+ *   "offload.d2h_on_compute" 1 = the staged ring copies back on `hip_stream`
  */
 zc_status zc_tune_set(const char *key, int64_t value);
 zc_status zc_tune_get(const char *key, int64_t *value_out);

@@ -307,7 +307,7 @@ static void pick_rows(int rows, bool g_bf16, bool nt, int arith, const VecLaunch
 
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
-                      hipStream_t stream)
+                      hipStream_t stream, int waves_per_cu)
 {
     if (n == 0)
         return ZC_OK;
@@ -327,7 +327,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
         if (ntiles == 0)
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
-        ZC_TRY(occupancy_cap_lds((int)t.adam_waves_per_cu, block, &lds));
+        ZC_TRY(occupancy_cap_lds(waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu, block, &lds));
         VecLaunch a{dim3(1), lds, stream, p, m, v, g, bf16_out, n, 0, s, skip_flag};
         const int64_t kMaxGrid = int64_t(1) << 30;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {

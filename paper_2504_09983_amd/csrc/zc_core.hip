@@ -135,6 +135,9 @@ static const Knob kKnobs[] = {
     {"cast.waves_per_cu", &Tune::cast_waves_per_cu, 0, 64},
     {"copy.nontemporal", &Tune::copy_nontemporal, 0, 1},
     {"offload.zero_copy", &Tune::offload_zero_copy, 0, 1},
+    {"offload.zc_waves_per_cu", &Tune::offload_zc_waves_per_cu, 0, 64},
+    {"offload.max_ahead", &Tune::offload_max_ahead, 0, 1},
+    {"offload.d2h_on_compute", &Tune::offload_d2h_on_compute, 0, 1},
 };
 
 static const Knob *find_knob(const char *key)

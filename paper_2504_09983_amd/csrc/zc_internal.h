@@ -36,7 +36,10 @@ struct Tune {
     int64_t copy_waves_per_cu = 16;
     int64_t cast_waves_per_cu = 24;
     int64_t copy_nontemporal = 1;
-    int64_t offload_zero_copy = 0;
+    int64_t offload_zero_copy = 1;
+    int64_t offload_zc_waves_per_cu = 0;
+    int64_t offload_max_ahead = 0;
+    int64_t offload_d2h_on_compute = 0;
 };
 Tune &tune();
 
@@ -53,9 +56,10 @@ zc_status check_hparams(const zc_adam_hparams *hp);
 zc_status check_dtype(zc_dtype t);
 
 // Enqueue the fused update over n elements; arguments already validated.
+// waves_per_cu < 0 takes the "adam.waves_per_cu" knob, otherwise overrides it.
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
-                      hipStream_t stream);
+                      hipStream_t stream, int waves_per_cu = -1);
 
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

@@ -64,11 +64,12 @@ def offload_vs_resident(n, n_res, chunk_bytes, nbuf, steps=2, g_bf16=True, zero_
     assert np.array_equal(host_u16(oout), oracle.cast_bf16(host_f32(rp)))
 
 
+@pytest.mark.parametrize("zero_copy", [False, True])
 @pytest.mark.parametrize("frac", [0.0, 0.25, 0.5, 1.0])
-def test_offload_equals_resident_fractions(frac):
+def test_offload_equals_resident_fractions(frac, zero_copy):
     n = 3 * (1 << 20) + 4099
     n_res = int(frac * n) // 1024 * 1024
-    offload_vs_resident(n, n_res, 1 << 20, 3)
+    offload_vs_resident(n, n_res, 1 << 20, 3, zero_copy=zero_copy)
 
 
 @pytest.mark.parametrize("nbuf", [1, 2, 3, 5])
@@ -92,6 +93,35 @@ def test_offload_64mib_chunks():
 
 def test_offload_zero_copy_mode():
     offload_vs_resident((1 << 20) + 77, 4096, 1 << 20, 3, zero_copy=True)
+    offload_vs_resident((1 << 22) + 3, 0, 1 << 20, 3, zero_copy=True, g_bf16=False, steps=3)
+    # misaligned host views force the scalar kernel through the link
+    n = 50001
+    base = [torch.zeros(n + 1, dtype=torch.float32, pin_memory=True) for _ in range(3)]
+    p0 = synth.host_params(n, 41)
+    base[0].numpy()[1:] = p0
+    views = [b[1:] for b in base]
+    g = oracle.cast_bf16(synth.host_grads_f32(n, 1))
+    dg = dev_u16(g)
+    out = torch.zeros(n, dtype=torch.int16, device=DEV)
+    ctx = zc.offload_create(1 << 16, 2)
+    old = zc.tune_get("offload.zero_copy")
+    try:
+        for mode in (1, 0):
+            zc.tune_set("offload.zero_copy", mode)
+            for b in base:
+                b.zero_()
+            base[0].numpy()[1:] = p0
+            ctx.adam_step(None, None, None, 0, *views, n, dg, zc.BF16, zc.hparams(step=1, **HP),
+                          bf16_out_dev=out)
+            sync()
+            op, om, ov = p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+            oracle.adam_step(op, om, ov, g, step=1, **HP)
+            assert_state_close(views[0].numpy(), views[1].numpy(), views[2].numpy(), op, om, ov,
+                               steps=1, tag=f"misaligned host, zero_copy={mode}")
+            assert all(float(b[0]) == 0.0 for b in base)
+    finally:
+        zc.tune_set("offload.zero_copy", old)
+        ctx.destroy()
 
 
 def test_offload_rejects_unpinned_host_memory():
