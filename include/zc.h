@@ -205,6 +205,9 @@ zc_status zc_offload_probe_link(zc_offload_ctx *ctx, const void *host_src, void 
  * g DEVICE fp32[n] or bf16[n]; sqnorm_out DEVICE float; found_inf_out DEVICE
  * int32, set to 1 when any element is NaN/Inf else 0.  Deterministic for a
  * given n (fixed reduction tree).  n == 0 writes 0 and 0.
+ * The per-workgroup partial sums live in a 64 KiB device workspace that the
+ * library allocates once per device on first use and keeps; calls on one device
+ * share it, so calls that overlap on different streams of one GPU race.
  */
 zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
                          int32_t *found_inf_out, void *hip_stream);
