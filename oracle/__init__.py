@@ -46,24 +46,28 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def _prepare(lib):
+    """Declare the argument types of a loaded oracle library."""
+    i64, f32, vp, i32 = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int
+    lib.zco_adam_step.argtypes = [vp, vp, vp, vp, i32, i64, f32, f32, f32, f32, f32,
+                                  f32, i64, i32, vp, i32]
+    lib.zco_adam_step.restype = None
+    lib.zco_cast_bf16.argtypes = [vp, vp, i64]
+    lib.zco_cast_bf16.restype = None
+    lib.zco_upcast_bf16.argtypes = [vp, vp, i64]
+    lib.zco_upcast_bf16.restype = None
+    lib.zco_grad_sqnorm.argtypes = [vp, i32, i64, ctypes.POINTER(ctypes.c_double),
+                                    ctypes.POINTER(ctypes.c_int32)]
+    lib.zco_grad_sqnorm.restype = None
+    lib.zco_unshard.argtypes = [vp, vp, vp, vp, i64]
+    lib.zco_unshard.restype = None
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        i64, f32, vp, i32 = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int
-        lib.zco_adam_step.argtypes = [vp, vp, vp, vp, i32, i64, f32, f32, f32, f32, f32,
-                                      f32, i64, i32, vp, i32]
-        lib.zco_adam_step.restype = None
-        lib.zco_cast_bf16.argtypes = [vp, vp, i64]
-        lib.zco_cast_bf16.restype = None
-        lib.zco_upcast_bf16.argtypes = [vp, vp, i64]
-        lib.zco_upcast_bf16.restype = None
-        lib.zco_grad_sqnorm.argtypes = [vp, i32, i64, ctypes.POINTER(ctypes.c_double),
-                                        ctypes.POINTER(ctypes.c_int32)]
-        lib.zco_grad_sqnorm.restype = None
-        lib.zco_unshard.argtypes = [vp, vp, vp, vp, i64]
-        lib.zco_unshard.restype = None
-        _lib = lib
+        _lib = _prepare(ctypes.CDLL(build()))
     return _lib
 
 
