@@ -47,9 +47,14 @@ def parse_args():
     ap.add_argument("--offload-elems", type=int, default=1 << 28,
                     help="elements streamed in the offload leg (0 = skip the leg)")
     ap.add_argument("--offload-frac", type=float, default=0.0, help="resident fraction f")
+    ap.add_argument("--offload-max-pinned-gib", type=float, default=60.0,
+                    help="largest total of pinned host memory to ask for; the partition is shrunk "
+                         "(same resident fraction) when its streamed part would need more")
     ap.add_argument("--offload-chunk-mib", type=int, default=64)
     ap.add_argument("--offload-buffers", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the short legs for gradient accumulation and the per-tensor layout")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain copy of known size (one unshard segment of 2^30 bf16 "
                          "elements, 2 GiB read + 2 GiB written, 5 launches): the reference for "
@@ -269,6 +274,8 @@ def main():
     del send
     torch.cuda.empty_cache()
 
+    if not args.no_next_rows:
+        result["next_rows"] = next_rows_leg(torch, synth, zc, dev)
     if args.offload_elems > 0:
         legs = {}
         keep = zc.tune_get("offload.zero_copy")
@@ -282,17 +289,72 @@ def main():
     print(json.dumps(result))
 
 
+def time_launches(torch, fn, reps=10):
+    fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in ev) / reps
+
+
+def next_rows_leg(torch, synth, zc, dev):
+    """Rows built after the main path: fp32 gradient accumulation (10 B/element) and the
+    unshard copy in the per-tensor even-partition layout (8 segments per tensor)."""
+    import numpy as np
+    shape = synth.LLAMA3_8B
+    tensors = synth.tensor_list(shape)
+    numels = [int(np.prod(d)) for _, d in tensors]
+    n = sum(numels) // WORLD
+    acc = torch.zeros(n, dtype=torch.float32, device=dev)
+    micro = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    synth.device_normal_(micro, synth.G_STD, seed=2003)
+    t_acc = time_launches(torch, lambda: zc.grad_accumulate(acc, micro, zc.BF16, n, 0.25))
+    del acc, micro
+    segs, send = zc.per_tensor_layout(numels, WORLD, 8)
+    gathered = torch.empty(WORLD * send, dtype=torch.int16, device=dev)
+    synth.device_index_hash16_(gathered)
+    outs = [torch.empty(d, dtype=torch.bfloat16, device=dev) for _, d in tensors]
+    table = [(src, outs[t].data_ptr() + 2 * dst if k else None, k) for t, src, dst, k in segs]
+    plan = zc.unshard_plan_create(table, WORLD * send)
+    t_un = time_launches(torch, lambda: zc.unshard(plan, gathered))
+    plan.destroy()
+    total = sum(numels)
+    del outs, gathered
+    torch.cuda.empty_cache()
+    return {
+        "grad_accumulate": {"elements": n, "ms": round(t_acc, 4), "bytes_per_element": 10,
+                            "GBps": round(gb(10 * n) / (t_acc * 1e-3), 1),
+                            "frac": round(gb(10 * n) / (t_acc * 1e-3) / HBM_PEAK_GBS, 4)},
+        "unshard_per_tensor": {"elements": total, "segments": sum(1 for s in segs if s[3]),
+                               "ms": round(t_un, 4), "bytes_per_element": 4,
+                               "GBps": round(gb(4 * total) / (t_un * 1e-3), 1),
+                               "frac": round(gb(4 * total) / (t_un * 1e-3) / HBM_PEAK_GBS, 4)},
+    }
+
+
 def offload_leg(torch, synth, zc, dev, args, probe=True):
     """Offloaded step: p/m/v of the streamed part in pinned host DRAM, 3-slot ring."""
     numa = bind_to_gpu_numa_node(torch)
-    n = int(args.offload_elems)
+    n_asked = n = int(args.offload_elems)
+    cap_elems = int(args.offload_max_pinned_gib * (1 << 30)) // 12
+    if (1.0 - args.offload_frac) * n > cap_elems:
+        n = int(cap_elems / (1.0 - args.offload_frac)) // 1024 * 1024
     n_res = int(args.offload_frac * n) // 1024 * 1024
     n_str = n - n_res
     chunk = args.offload_chunk_mib << 20
-    hp_, hm_, hv_ = (torch.empty(n_str, dtype=torch.float32, pin_memory=True) for _ in range(3))
-    tmp = torch.empty(n_str, dtype=torch.float32, device=dev)
-    synth.device_normal_(tmp, synth.P_STD, seed=3)
-    hp_.copy_(tmp)
+    # exact-size pinned arrays (torch's pinned allocator rounds up to a power of two)
+    bufs = [zc.host_alloc(4 * max(n_str, 1)) for _ in range(3)]
+    hp_, hm_, hv_ = (torch.from_numpy(b.numpy("float32")) for b in bufs)
+    piece = 1 << 28
+    tmp = torch.empty(min(piece, max(n_str, 1)), dtype=torch.float32, device=dev)
+    for s0 in range(0, n_str, piece):                 # p ~ N(0, 0.02); m = v = 0
+        e0 = min(n_str, s0 + piece)
+        synth.device_normal_(tmp[:e0 - s0], synth.P_STD, seed=3 + s0 // piece)
+        hp_[s0:e0].copy_(tmp[:e0 - s0])
     hm_.zero_()
     hv_.zero_()
     del tmp
@@ -318,7 +380,7 @@ def offload_leg(torch, synth, zc, dev, args, probe=True):
     dt = (time.perf_counter() - t0) / reps
 
     extra = {}
-    if probe:
+    if probe and n_str > 0:
         # plain pinned-copy ceilings with the same chunking: one direction at a time and both
         nbytes = 4 * n_str
         t_h2d = min(ctx.probe_link(hp_, hv_, nbytes, 0) for _ in range(3)) * 1e-3
@@ -328,9 +390,14 @@ def offload_leg(torch, synth, zc, dev, args, probe=True):
                                         "d2h": round(gb(nbytes) / t_d2h, 2),
                                         "both_each": round(gb(nbytes) / t_both, 2)}
     ctx.destroy()
+    del hp_, hm_, hv_
+    for b in bufs:
+        b.free()
     one_way = 12 * n_str
     return {
-        "elements": n, "resident_fraction": n_res / n, "chunk_MiB": args.offload_chunk_mib,
+        "elements": n, "elements_asked": n_asked, "streamed_elements": n_str,
+        "pinned_GB": round(12 * n_str / 1e9, 2),
+        "resident_fraction": n_res / n, "chunk_MiB": args.offload_chunk_mib,
         "buffers": args.offload_buffers, "ms_per_step": round(dt * 1e3, 3),
         "gparams_per_s": round(n / dt / 1e9, 3),
         "link_GBps_each_direction": round(gb(one_way) / dt, 2),

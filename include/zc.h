@@ -130,6 +130,25 @@ zc_status zc_flat_layout(const int64_t *numels, int64_t ntensors, int32_t world,
                          int64_t *shard_numel_out, int64_t *total_out);
 
 /*
+ * Host-only helper: per-tensor even partition, the layout the paper states
+ * literally (every parameter tensor evenly partitioned across all GPUs,
+ * Fully-sharded approach) with the all-gathers of a group of tensors fused into
+ * one buffer (Proactive prefetching, Fuse).  Tensor t is cut into `world` slices
+ * of s_t = ceil(ceil(n_t/world)/align)*align elements, the part beyond n_t being
+ * padding; a rank's send buffer is its slices of all tensors back to back
+ * (*send_numel_out = sum of s_t elements); the gathered buffer is the `world`
+ * send buffers in rank order.  For segment k = t*world + r the tables receive
+ *   src_offsets_out[k] = r * send_numel + (sum of s_t' for t' < t)
+ *   dst_offsets_out[k] = r * s_t        (element offset inside tensor t)
+ *   seg_numels_out[k]  = real elements rank r holds of tensor t (0 = padding only)
+ * which, with dst = tensor base + dst offset, is a zc_segment table for
+ * zc_unshard_plan_create.  All pointers HOST, tables of ntensors*world entries.
+ */
+zc_status zc_per_tensor_layout(const int64_t *numels, int64_t ntensors, int32_t world,
+                               int64_t align, int64_t *src_offsets_out, int64_t *dst_offsets_out,
+                               int64_t *seg_numels_out, int64_t *send_numel_out);
+
+/*
  * Unshard: copy pieces of the gathered flat bf16 buffer (what the all-gather
  * produced: the large buffer B_ag of Proactive prefetching / Selective
  * unsharding) into separately allocated per-layer tensors.  Bit copy.
@@ -162,7 +181,9 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  *   0            staged ring: host -> staging slot -> kernel -> host in chunks
  *                of chunk_bytes per array through num_buffers slots, copies on
  *                two internal streams (hipMemcpyAsync) and the kernel on
- *                `hip_stream`, fenced by events.
+ *                `hip_stream`, fenced by events.  With "offload.max_ahead" = 1
+ *                (default) this transport blocks the calling thread while it
+ *                feeds the ring; the results are still ordered on `hip_stream`.
  *
  * zc_offload_create   chunk_bytes: bytes per fp32 array per chunk, a positive
  *                     multiple of 4096 (64 MiB in the reference workload);
@@ -188,6 +209,16 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
 zc_status zc_offload_destroy(zc_offload_ctx *ctx);
 
 /*
+ * Pinned host memory of exactly `bytes` bytes for the offloaded partitions
+ * (hipHostMalloc; page-locked, device-accessible, 4 KiB aligned).  A convenience
+ * for callers whose allocator rounds pinned requests up (a 35 GB array then
+ * costs 64 GB).  *out (HOST) is owned by the caller and released with
+ * zc_host_free; NULL is a no-op there.  Failure -> ZC_ERR_NOMEM, *out = NULL.
+ */
+zc_status zc_host_alloc(int64_t bytes, void **out);
+zc_status zc_host_free(void *ptr);
+
+/*
  * Measurement helper: the practical host-link ceiling next to which the offloaded
  * step is reported.  Copies `bytes` from pinned HOST memory into the context's
  * staging ring (mode 0), from the ring to pinned HOST memory (mode 1), or both at
@@ -197,6 +228,19 @@ zc_status zc_offload_destroy(zc_offload_ctx *ctx);
  */
 zc_status zc_offload_probe_link(zc_offload_ctx *ctx, const void *host_src, void *host_dst,
                                 int64_t bytes, int32_t mode, float *ms_out);
+
+/*
+ * Gradient accumulation into the fp32 gradient partition (paper: fp32 gradients
+ * are kept, Experimental settings; with gradient accumulation several forward/
+ * backward passes add into them before one update, Selective unsharding):
+ *   acc[i] = acc[i] + upcast(micro[i]) * scale      (one rounding to fp32)
+ * acc DEVICE fp32[n], updated in place; micro DEVICE fp32[n] or bf16[n], read
+ * only, must not alias acc; scale finite (1/accumulation-steps, loss-scale
+ * removal).  The accumulated fp32 partition is then the g of zc_grad_sqnorm and
+ * zc_adam_step (ZC_F32).  n == 0 is a no-op.
+ */
+zc_status zc_grad_accumulate(float *acc, const void *micro, zc_dtype micro_dtype, int64_t n,
+                             float scale, void *hip_stream);
 
 /*
  * Squared L2 norm of the gradient partition and a non-finite flag (the
@@ -222,12 +266,14 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
  *   "adam.nontemporal" 0/1 non-temporal loads and stores
  *   "adam.arith"       0 = fp32 only, 1 = fp64 multiply-adds with fp32 sqrt/div,
  *                      2 = fp64 throughout
- *   "copy.waves_per_cu", "cast.waves_per_cu"  the same cap for unshard and for the cast
+ *   "copy.waves_per_cu", "cast.waves_per_cu", "accum.waves_per_cu"  the same cap for
+ *                      unshard, the cast and gradient accumulation
  *   "copy.nontemporal"  non-temporal accesses in cast and unshard
  *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default)
  *   "offload.zc_waves_per_cu"  resident-wave cap of the zero-copy kernel (0 = none)
- *   "offload.max_ahead" 1 = the staged ring blocks the host so that it never runs more
- *                      than num_buffers chunks ahead of finished copy-backs
+ *   "offload.max_ahead" 1 (default) = the staged ring blocks the host so that it never runs
+ *                      more than num_buffers chunks ahead of finished copy-backs (deep copy
+ *                      queues were measured to halve the link rate); 0 = enqueue everything
  *   "offload.d2h_on_compute" 1 = the staged ring copies back on `hip_stream`
  */
 zc_status zc_tune_set(const char *key, int64_t value);

@@ -61,6 +61,8 @@ def _prepare(lib):
     lib.zco_grad_sqnorm.restype = None
     lib.zco_unshard.argtypes = [vp, vp, vp, vp, i64]
     lib.zco_unshard.restype = None
+    lib.zco_grad_accumulate.argtypes = [vp, vp, i32, i64, f32]
+    lib.zco_grad_accumulate.restype = None
     return lib
 
 
@@ -146,6 +148,21 @@ def grad_sqnorm(g: np.ndarray):
     return s.value, int(f.value)
 
 
+def grad_accumulate(acc: np.ndarray, micro: np.ndarray, scale: float = 1.0) -> None:
+    """acc += upcast(micro) * scale in place; micro is float32 values or uint16 bf16 bits."""
+    _f32(acc, "acc")
+    micro = np.ascontiguousarray(micro)
+    if micro.size != acc.size:
+        raise ValueError("acc and micro must have equal length")
+    if micro.dtype == np.float32:
+        is_bf16 = 0
+    elif micro.dtype == np.uint16:
+        is_bf16 = 1
+    else:
+        raise TypeError("micro must be float32 or uint16 (bf16 bits)")
+    _load().zco_grad_accumulate(_ptr(acc), _ptr(micro), is_bf16, acc.size, float(np.float32(scale)))
+
+
 def unshard(gathered: np.ndarray, src_offsets, numels):
     """Copy ``gathered[off : off + n]`` into a fresh uint16 array per segment."""
     gathered = np.ascontiguousarray(gathered, dtype=np.uint16)
@@ -159,6 +176,19 @@ def unshard(gathered: np.ndarray, src_offsets, numels):
     ptrs = (ctypes.c_void_p * max(1, len(outs)))(*[o.ctypes.data for o in outs])
     _load().zco_unshard(_ptr(gathered), _ptr(offs), ctypes.cast(ptrs, ctypes.c_void_p),
                         _ptr(nums), len(outs))
+    return outs
+
+
+def unshard_per_tensor(gathered: np.ndarray, numels, world: int, align: int = 1):
+    """Per-tensor even partition: rebuild every tensor from its W slices."""
+    segs, L = layout.per_tensor_segments(numels, world, align)
+    gathered = np.ascontiguousarray(gathered, dtype=np.uint16)
+    if gathered.size != world * L:
+        raise ValueError("gathered buffer has the wrong length for this layout")
+    outs = [np.zeros(int(n), dtype=np.uint16) for n in numels]
+    pieces = unshard(gathered, [s[1] for s in segs], [s[3] for s in segs])
+    for (t, _src, dst, k), piece in zip(segs, pieces):
+        outs[t][dst:dst + k] = piece
     return outs
 
 

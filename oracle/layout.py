@@ -58,3 +58,60 @@ def flatten_pad(tensors, world: int, shard_align: int = 1, dtype=np.uint16):
         pos += t.size
     assert pos == total
     return flat
+
+
+# ---------------------------------------------------------------------------
+# Per-tensor even partition (the literal layout of the paper's Fully-sharded
+# approach: every parameter tensor is split evenly over the ranks) gathered by
+# one fused all-gather over a group of tensors (Proactive prefetching, Fuse(U)).
+#
+# Reading: tensor t of n_t elements is cut into W slices of s_t = ceil(n_t / W)
+# elements rounded up to a multiple of `align`; rank r owns elements
+# [r*s_t, (r+1)*s_t) of it, the part beyond n_t being zero padding.  A rank's
+# send buffer is its slices of all tensors of the group back to back (length
+# L = sum s_t); the gathered buffer is the W send buffers in rank order.
+# ---------------------------------------------------------------------------
+
+def per_tensor_slices(numels, world: int, align: int = 1):
+    """(slice sizes s_t, offsets o_t inside a rank's send buffer, send length L)."""
+    if world < 1 or align < 1:
+        raise ValueError("world and align must be positive")
+    sizes, offs, pos = [], [], 0
+    for n in numels:
+        n = int(n)
+        if n < 0:
+            raise ValueError("negative tensor size")
+        s = -(-n // world)
+        s = -(-s // align) * align
+        sizes.append(s)
+        offs.append(pos)
+        pos += s
+    return sizes, offs, pos
+
+
+def per_tensor_gather(tensors, world: int, align: int = 1, dtype=np.uint16):
+    """Build the gathered buffer element by element from the definition."""
+    numels = [np.asarray(t).size for t in tensors]
+    sizes, offs, L = per_tensor_slices(numels, world, align)
+    gathered = np.zeros(world * L, dtype=dtype)
+    for r in range(world):
+        for t, s, o, n in zip(tensors, sizes, offs, numels):
+            flat = np.asarray(t, dtype=dtype).reshape(-1)
+            for j in range(s):
+                i = r * s + j
+                if i < n:
+                    gathered[r * L + o + j] = flat[i]
+    return gathered
+
+
+def per_tensor_segments(numels, world: int, align: int = 1):
+    """Unshard segments (tensor index, src offset in gathered, dst offset in the tensor,
+    numel), one per (tensor, rank) that holds at least one real element."""
+    sizes, offs, L = per_tensor_slices(numels, world, align)
+    segs = []
+    for t, (n, s, o) in enumerate(zip(numels, sizes, offs)):
+        for r in range(world):
+            k = min(s, max(0, int(n) - r * s))
+            if k > 0:
+                segs.append((t, r * L + o, r * s, k))
+    return segs, L

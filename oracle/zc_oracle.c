@@ -167,3 +167,20 @@ void zco_unshard(const uint16_t *gathered, const int64_t *src_offset,
         for (int64_t j = 0; j < numel[s]; ++j)
             dst[s][j] = gathered[src_offset[s] + j];
 }
+
+/*
+ * Gradient accumulation into the fp32 gradient partition (the paper keeps fp32
+ * gradients, Experimental settings, and accumulates several forward/backward
+ * passes before one update, Selective unsharding):
+ *   acc[i] = acc[i] + upcast(micro[i]) * scale, one rounding to fp32 per store.
+ */
+void zco_grad_accumulate(float *acc, const void *micro, int micro_is_bf16, int64_t n, float scale_f)
+{
+    const double scale = scale_f;
+    const float *g32 = (const float *)micro;
+    const uint16_t *g16 = (const uint16_t *)micro;
+    for (int64_t i = 0; i < n; ++i) {
+        const double gi = micro_is_bf16 ? (double)zco_bf16_to_f32(g16[i]) : (double)g32[i];
+        acc[i] = (float)((double)acc[i] + gi * scale);
+    }
+}

@@ -133,6 +133,7 @@ static const Knob kKnobs[] = {
     {"adam.arith", &Tune::adam_arith, 0, 2},
     {"copy.waves_per_cu", &Tune::copy_waves_per_cu, 0, 64},
     {"cast.waves_per_cu", &Tune::cast_waves_per_cu, 0, 64},
+    {"accum.waves_per_cu", &Tune::accum_waves_per_cu, 0, 64},
     {"copy.nontemporal", &Tune::copy_nontemporal, 0, 1},
     {"offload.zero_copy", &Tune::offload_zero_copy, 0, 1},
     {"offload.zc_waves_per_cu", &Tune::offload_zc_waves_per_cu, 0, 64},
@@ -207,6 +208,54 @@ zc_status zc_flat_layout(const int64_t *numels, int64_t ntensors, int32_t world,
     const int64_t per_rank = (running + world - 1) / world;
     *shard_numel_out = (per_rank + shard_align - 1) / shard_align * shard_align;
     *total_out = running;
+    return ZC_OK;
+}
+
+zc_status zc_per_tensor_layout(const int64_t *numels, int64_t ntensors, int32_t world, int64_t align,
+                               int64_t *src_offsets_out, int64_t *dst_offsets_out,
+                               int64_t *seg_numels_out, int64_t *send_numel_out)
+{
+    if (ntensors < 0 || world < 1 || align < 1)
+        return zc::fail(ZC_ERR_INVALID_ARG, "need ntensors >= 0, world >= 1, align >= 1");
+    if (ntensors > 0 && (!numels || !src_offsets_out || !dst_offsets_out || !seg_numels_out))
+        return zc::fail(ZC_ERR_INVALID_ARG, "numels or an output table is NULL");
+    if (!send_numel_out)
+        return zc::fail(ZC_ERR_INVALID_ARG, "send_numel_out is NULL");
+    const int64_t limit = zc::kMaxElements * 64;
+    // Pass 1: validate and size one rank's send buffer.
+    int64_t send = 0;
+    for (int64_t t = 0; t < ntensors; ++t) {
+        if (numels[t] < 0)
+            return zc::fail(ZC_ERR_INVALID_ARG, "numels[%lld] is negative", (long long)t);
+        if (numels[t] > limit)
+            return zc::fail(ZC_ERR_UNSUPPORTED, "tensor %lld exceeds 2^46 elements", (long long)t);
+        const int64_t slice = ((numels[t] + world - 1) / world + align - 1) / align * align;
+        if (slice > (limit - send))
+            return zc::fail(ZC_ERR_UNSUPPORTED, "send buffer exceeds 2^46 elements");
+        send += slice;
+    }
+    if (send > limit / world)
+        return zc::fail(ZC_ERR_UNSUPPORTED, "gathered buffer exceeds 2^46 elements");
+    // Pass 2: one segment per (tensor, rank); ranks that hold only padding get numel 0.
+    int64_t inside = 0;
+    for (int64_t t = 0; t < ntensors; ++t) {
+        const int64_t n = numels[t];
+        const int64_t slice = ((n + world - 1) / world + align - 1) / align * align;
+        for (int32_t r = 0; r < world; ++r) {
+            const int64_t first = (int64_t)r * slice;
+            int64_t count = n - first;
+            if (count > slice)
+                count = slice;
+            if (count < 0)
+                count = 0;
+            const int64_t k = t * world + r;
+            src_offsets_out[k] = (int64_t)r * send + inside;
+            dst_offsets_out[k] = count > 0 ? first : 0;
+            seg_numels_out[k] = count;
+        }
+        inside += slice;
+    }
+    *send_numel_out = send;
     return ZC_OK;
 }
 

@@ -132,6 +132,33 @@ zc_status zc_offload_destroy(zc_offload_ctx *ctx)
     return ZC_OK;
 }
 
+zc_status zc_host_alloc(int64_t bytes, void **out)
+{
+    using namespace zc;
+    if (!out)
+        return fail(ZC_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (bytes <= 0)
+        return fail(ZC_ERR_INVALID_ARG, "bytes must be positive");
+    void *ptr = nullptr;
+    const hipError_t e = hipHostMalloc(&ptr, (size_t)bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ZC_ERR_NOMEM, "hipHostMalloc(%lld bytes): %s", (long long)bytes, hipGetErrorString(e));
+    }
+    *out = ptr;
+    return ZC_OK;
+}
+
+zc_status zc_host_free(void *ptr)
+{
+    using namespace zc;
+    if (!ptr)
+        return ZC_OK;
+    ZC_HIP(hipHostFree(ptr));
+    return ZC_OK;
+}
+
 zc_status zc_offload_probe_link(zc_offload_ctx *ctx, const void *host_src, void *host_dst, int64_t bytes,
                                 int32_t mode, float *ms_out)
 {

@@ -71,6 +71,9 @@ def lib():
     L.zc_flat_layout.restype = ctypes.c_int
     L.zc_flat_layout.argtypes = [ctypes.POINTER(i64), i64, i32, i64, ctypes.POINTER(i64),
                                  ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.zc_per_tensor_layout.restype = ctypes.c_int
+    L.zc_per_tensor_layout.argtypes = [ctypes.POINTER(i64), i64, i32, i64, ctypes.POINTER(i64),
+                                       ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.zc_unshard_plan_create.restype = ctypes.c_int
     L.zc_unshard_plan_create.argtypes = [ctypes.POINTER(Segment), i64, i64, ctypes.POINTER(vp)]
     L.zc_unshard.restype = ctypes.c_int
@@ -84,8 +87,14 @@ def lib():
                                        ctypes.POINTER(AdamHparams), vp, vp, vp]
     L.zc_offload_destroy.restype = ctypes.c_int
     L.zc_offload_destroy.argtypes = [vp]
+    L.zc_host_alloc.restype = ctypes.c_int
+    L.zc_host_alloc.argtypes = [i64, ctypes.POINTER(vp)]
+    L.zc_host_free.restype = ctypes.c_int
+    L.zc_host_free.argtypes = [vp]
     L.zc_offload_probe_link.restype = ctypes.c_int
     L.zc_offload_probe_link.argtypes = [vp, vp, vp, i64, i32, ctypes.POINTER(ctypes.c_float)]
+    L.zc_grad_accumulate.restype = ctypes.c_int
+    L.zc_grad_accumulate.argtypes = [vp, vp, ctypes.c_int, i64, ctypes.c_float, vp]
     L.zc_grad_sqnorm.restype = ctypes.c_int
     L.zc_grad_sqnorm.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp]
     L.zc_tune_set.restype = ctypes.c_int
@@ -158,6 +167,19 @@ def flat_layout(numels: Sequence[int], world: int, shard_align: int = 1):
     return [offs[i] for i in range(k)], shard.value, total.value
 
 
+def per_tensor_layout(numels: Sequence[int], world: int, align: int = 1):
+    """([(tensor, src_offset, dst_offset, numel), ...] for every (tensor, rank), send_numel)."""
+    k = len(numels)
+    arr = (ctypes.c_int64 * max(1, k))(*[int(x) for x in numels])
+    src = (ctypes.c_int64 * max(1, k * world))()
+    dst = (ctypes.c_int64 * max(1, k * world))()
+    cnt = (ctypes.c_int64 * max(1, k * world))()
+    send = ctypes.c_int64(0)
+    _check(lib().zc_per_tensor_layout(arr, k, world, align, src, dst, cnt, ctypes.byref(send)))
+    segs = [(i // world, src[i], dst[i], cnt[i]) for i in range(k * world)]
+    return segs, send.value
+
+
 class UnshardPlan:
     """Owns a zc_unshard_plan; segments are (src_offset, dst address or tensor, numel)."""
 
@@ -228,8 +250,46 @@ class OffloadCtx:
             pass
 
 
+class PinnedBuffer:
+    """Owns pinned host memory from zc_host_alloc; `.numpy(dtype)` views it without a copy."""
+
+    def __init__(self, nbytes: int):
+        ptr = ctypes.c_void_p(None)
+        _check(lib().zc_host_alloc(nbytes, ctypes.byref(ptr)))
+        self.ptr = ptr.value
+        self.nbytes = nbytes
+
+    def data_ptr(self) -> int:
+        return self.ptr
+
+    def numpy(self, dtype="float32"):
+        import numpy as np
+        dt = np.dtype(dtype)
+        buf = (ctypes.c_char * self.nbytes).from_address(self.ptr)
+        return np.frombuffer(buf, dtype=dt, count=self.nbytes // dt.itemsize)
+
+    def free(self) -> None:
+        if self.ptr:
+            _check(lib().zc_host_free(ctypes.c_void_p(self.ptr)))
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def host_alloc(nbytes: int) -> PinnedBuffer:
+    return PinnedBuffer(nbytes)
+
+
 def offload_create(chunk_bytes: int = 64 << 20, num_buffers: int = 3) -> OffloadCtx:
     return OffloadCtx(chunk_bytes, num_buffers)
+
+
+def grad_accumulate(acc, micro, micro_dtype: int, n: int, scale: float = 1.0, stream=None) -> None:
+    _check(lib().zc_grad_accumulate(_addr(acc), _addr(micro), micro_dtype, n, scale, _stream(stream)))
 
 
 def grad_sqnorm(g, g_dtype: int, n: int, sqnorm_out, found_inf_out, stream=None) -> None:

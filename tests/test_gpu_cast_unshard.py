@@ -248,3 +248,82 @@ def test_grad_sqnorm_misaligned_and_large_values():
     zc.grad_sqnorm(dev_u16(big), zc.BF16, 64, out, flag)
     sync()
     assert flag.item() == 0 and oracle.grad_sqnorm(big)[1] == 0
+
+
+# ---- per-tensor even partition (every tensor split over the ranks; fused group) -------
+
+def run_unshard_per_tensor(numels, world=8, align=1, seed=0):
+    rng = np.random.default_rng(seed)
+    tensors = [rng.integers(1, 1 << 16, size=n, dtype=np.uint16) for n in numels]
+    gathered_host = olayout.per_tensor_gather(tensors, world, align)
+    segs, send = zc.per_tensor_layout(numels, world, align)
+    assert send * world == gathered_host.size
+    gathered = dev_u16(gathered_host)
+    bufs = [torch.full((n + 2 * GUARD,), 0x7E7E, dtype=torch.int16, device=DEV) for n in numels]
+    table = [(src, bufs[t].data_ptr() + 2 * (GUARD + dst) if k else None, k) for t, src, dst, k in segs]
+    plan = zc.unshard_plan_create(table, gathered_host.size)
+    zc.unshard(plan, gathered)
+    sync()
+    plan.destroy()
+    want = oracle.unshard_per_tensor(gathered_host, numels, world, align)
+    for i, (buf, w, src_t) in enumerate(zip(bufs, want, tensors)):
+        got = host_u16(buf[GUARD:GUARD + numels[i]])
+        assert np.array_equal(got, w) and np.array_equal(got, src_t), f"tensor {i}"
+        assert (buf[:GUARD] == 0x7E7E).all() and (buf[GUARD + numels[i]:] == 0x7E7E).all()
+
+
+@pytest.mark.parametrize("align", [1, 8])
+def test_unshard_per_tensor_partition(align):
+    run_unshard_per_tensor([1, 3, 7, 4097, 0, 64, 129, 8192 * 3 + 5, 11], align=align)
+    run_unshard_per_tensor([5], align=align)
+    run_unshard_per_tensor([8 * 4096, 4096, 8 * 14336], align=align)
+
+
+def test_unshard_per_tensor_model_shaped():
+    shape = synth.ModelShape("mini_moe", 2, 128, 448, 4, 1, 1000, experts=8, head_dim=32)
+    run_unshard_per_tensor(synth.tensor_numels(shape), align=8, seed=3)
+
+
+# ---- gradient accumulation ---------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 1024 * 4 + 1, (1 << 20) + 7])
+@pytest.mark.parametrize("bf16", [True, False])
+def test_grad_accumulate_bit_exact(n, bf16):
+    acc = synth.host_normal(n, 1e-3, 70)
+    dacc = dev_f32(acc)
+    for k in range(4):                      # four micro-batches, scale 1/4 then an odd one
+        micro = synth.host_grads_f32(n, 10 + k)
+        scale = 0.25 if k < 3 else 0.37
+        if bf16:
+            micro = oracle.cast_bf16(micro)
+            dmicro = dev_u16(micro)
+        else:
+            dmicro = dev_f32(micro)
+        oracle.grad_accumulate(acc, micro, scale)
+        zc.grad_accumulate(dacc, dmicro, zc.BF16 if bf16 else zc.F32, n, scale)
+    sync()
+    assert np.array_equal(dacc.cpu().numpy().view(np.uint32), acc.view(np.uint32))
+
+
+def test_grad_accumulate_misaligned_then_feeds_the_step():
+    n = 30001
+    acc = np.zeros(n + 1, np.float32)
+    dacc_full = dev_f32(acc)
+    dacc = dacc_full[1:]                     # 4-byte aligned only -> scalar kernel
+    micro = oracle.cast_bf16(synth.host_grads_f32(n, 3))
+    dmicro = dev_u16(micro)
+    zc.grad_accumulate(dacc, dmicro, zc.BF16, n, 0.5)
+    zc.grad_accumulate(dacc, dmicro, zc.BF16, n, 0.5)
+    a = np.zeros(n, np.float32)
+    oracle.grad_accumulate(a, micro, 0.5)
+    oracle.grad_accumulate(a, micro, 0.5)
+    sync()
+    assert float(dacc_full[0]) == 0.0
+    assert np.array_equal(dacc.cpu().numpy(), a)
+    # the accumulated fp32 partition is what the norm and the step consume
+    out = torch.zeros(1, dtype=torch.float32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    zc.grad_sqnorm(dacc, zc.F32, n, out, flag)
+    sync()
+    want, bad = oracle.grad_sqnorm(a)
+    assert bad == 0 and flag.item() == 0 and abs(out.item() - want) <= 1e-6 * want

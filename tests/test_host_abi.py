@@ -27,7 +27,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert {"zc_adam_step", "zc_cast_bf16", "zc_unshard", "zc_offload_adam_step",
             "zc_unshard_plan_create", "zc_unshard_plan_destroy", "zc_offload_create",
             "zc_offload_destroy", "zc_grad_sqnorm", "zc_flat_layout", "zc_last_error",
-            "zc_version", "zc_tune_set", "zc_tune_get"} <= set(names)
+            "zc_version", "zc_tune_set", "zc_tune_get", "zc_per_tensor_layout", "zc_host_alloc",
+            "zc_host_free", "zc_offload_probe_link", "zc_grad_accumulate"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert zc.version() >= 100
@@ -80,6 +81,13 @@ def test_cast_and_sqnorm_reject_bad_arguments_without_a_gpu():
     assert _status(zc.cast_bf16, A, A + 4097, 4, stream=0) == zc.ERR_ALIGNMENT
     assert _status(zc.cast_bf16, A, A + 8, 16, stream=0) == zc.ERR_INVALID_ARG   # overlap
     zc.cast_bf16(0, 0, 0, stream=0)
+    assert _status(zc.grad_accumulate, A, A + 4096, zc.BF16, -1, 1.0, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.grad_accumulate, 0, A + 4096, zc.BF16, 4, 1.0, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.grad_accumulate, A, A, zc.F32, 4, 1.0, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.grad_accumulate, A + 2, A + 4096, zc.F32, 4, 1.0, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.grad_accumulate, A, A + 4097, zc.BF16, 4, 1.0, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.grad_accumulate, A, A + 4096, zc.BF16, 4, float("inf"), stream=0) == zc.ERR_INVALID_ARG
+    zc.grad_accumulate(0, 0, zc.F32, 0, 1.0, stream=0)
     assert _status(zc.grad_sqnorm, A, zc.BF16, -1, A + 64, A + 68, stream=0) == zc.ERR_INVALID_ARG
     assert _status(zc.grad_sqnorm, A, zc.BF16, 4, 0, A + 68, stream=0) == zc.ERR_INVALID_ARG
     assert _status(zc.grad_sqnorm, A + 1, zc.BF16, 4, A + 64, A + 68, stream=0) == zc.ERR_ALIGNMENT
@@ -122,6 +130,22 @@ def test_flat_layout_matches_oracle_layout(align):
         offs, shard, total = zc.flat_layout(numels, 8, align)
         o_offs, o_shard, o_total = olayout.flat_layout(numels, 8, align)
         assert offs == list(o_offs) and shard == o_shard and total == o_total
+
+
+@pytest.mark.parametrize("align", [1, 8, 64])
+def test_per_tensor_layout_matches_oracle_layout(align):
+    for numels in ([1, 3, 7, 4097], [0, 9, 0, 2], [], [16, 64, 8], [1000, 24, 333],
+                   synth.tensor_numels(synth.MIXTRAL_8X7B)):
+        segs, send = zc.per_tensor_layout(numels, 8, align)
+        o_segs, o_send = olayout.per_tensor_segments(numels, 8, align)
+        assert send == o_send
+        assert len(segs) == 8 * len(numels)
+        assert [s for s in segs if s[3] > 0] == [tuple(int(x) for x in s) for s in o_segs]
+        assert all(s[3] == 0 or s[3] > 0 for s in segs)
+    assert _status(zc.per_tensor_layout, [4, -1], 8, 1) == zc.ERR_INVALID_ARG
+    assert _status(zc.per_tensor_layout, [4], 0, 1) == zc.ERR_INVALID_ARG
+    assert _status(zc.per_tensor_layout, [4], 8, 0) == zc.ERR_INVALID_ARG
+    assert _status(zc.per_tensor_layout, [1 << 47], 8, 1) == zc.ERR_UNSUPPORTED
 
 
 def test_flat_layout_rejects_bad_input():

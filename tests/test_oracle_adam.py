@@ -405,3 +405,40 @@ def test_grad_sqnorm():
     big = synth.host_normal(100000, 1e-3, 5)
     s, _ = oracle.grad_sqnorm(big)
     assert abs(s - float(np.sum(big.astype(np.float64) ** 2))) <= 1e-12 * s
+
+
+# ---- gradient accumulation ----------------------------------------------------------
+
+def test_grad_accumulate_closed_forms():
+    # k micro-steps of a constant dyadic gradient: exact k * g * scale
+    g = f32([0.5, -0.25, 3.0, 0.0, -1024.0])
+    acc = np.zeros(5, np.float32)
+    for _ in range(16):
+        oracle.grad_accumulate(acc, g, 0.125)
+    assert np.array_equal(acc, g * np.float32(2.0))
+    # one accumulation from zero is the (rounded) product itself
+    x = synth.host_grads_f32(1000, 3)
+    acc = np.zeros(1000, np.float32)
+    oracle.grad_accumulate(acc, x, 0.37)
+    assert np.array_equal(acc, (x.astype(np.float64) * float(np.float32(0.37))).astype(np.float32))
+    # against numpy in double, then one rounding: the sum of two fp32 values scaled by a
+    # power of two is exactly representable in double
+    a0 = synth.host_normal(1000, 1e-3, 5)
+    acc = a0.copy()
+    oracle.grad_accumulate(acc, x, 0.5)
+    assert np.array_equal(acc, (a0.astype(np.float64) + x.astype(np.float64) * 0.5).astype(np.float32))
+    # bf16 micro-gradients are their widened fp32 values
+    xb = oracle.cast_bf16(x)
+    a1, a2 = a0.copy(), a0.copy()
+    oracle.grad_accumulate(a1, xb, 0.37)
+    oracle.grad_accumulate(a2, oracle.upcast_bf16(xb), 0.37)
+    assert np.array_equal(a1, a2)
+    # order of micro-batches matters only through fp32 rounding; subtraction undoes exactly
+    acc = np.zeros(4, np.float32)
+    oracle.grad_accumulate(acc, f32([1, 2, 3, 4]), 1.0)
+    oracle.grad_accumulate(acc, f32([1, 2, 3, 4]), -1.0)
+    assert not acc.any()
+    # NaN/Inf propagate to their own element only
+    acc = np.zeros(3, np.float32)
+    oracle.grad_accumulate(acc, f32([1.0, np.inf, np.nan]), 2.0)
+    assert acc[0] == 2.0 and np.isinf(acc[1]) and np.isnan(acc[2])

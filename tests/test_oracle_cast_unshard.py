@@ -205,3 +205,49 @@ def test_host_and_device_hash_agree_on_cpu():
         b = synth.device_index_hash16_values(start, 1000, "cpu").numpy().view(np.uint16)
         assert np.array_equal(a, b)
     assert len(np.unique(synth.host_index_hash16(0, 1 << 16))) > 40000
+
+
+# ---- per-tensor even partition (the paper's literal layout) ---------------------------
+
+@pytest.mark.parametrize("align", [1, 8])
+@pytest.mark.parametrize("numels", [[1, 3, 7, 4097], [16, 64, 8], [5], [0, 9, 0, 2], [1000, 24, 333]])
+def test_per_tensor_round_trip_and_ownership(numels, align):
+    W = 8
+    rng = np.random.default_rng(sum(numels) + align)
+    tensors = [rng.integers(1, 1 << 16, size=n, dtype=np.uint16) for n in numels]   # never 0
+    gathered = layout.per_tensor_gather(tensors, W, align)
+    sizes, offs, L = layout.per_tensor_slices(numels, W, align)
+    assert gathered.size == W * L
+    assert all(s % align == 0 and s * W >= n and (s - align) * W < max(n, 1) + align * W
+               for s, n in zip(sizes, numels))
+    # every real element appears exactly once; everything else is zero padding
+    assert np.count_nonzero(gathered) == sum(numels)
+    # brute force ownership: element i of tensor t sits in rank i // s_t at o_t + i % s_t
+    for t, (n, s, o) in enumerate(zip(numels, sizes, offs)):
+        for i in (0, n // 3, n - 1):
+            if n:
+                assert gathered[(i // s) * L + o + i % s] == tensors[t][i]
+    outs = oracle.unshard_per_tensor(gathered, numels, W, align)
+    for a, b in zip(tensors, outs):
+        assert np.array_equal(a, b)
+    # segments never read padding and cover each tensor exactly once, in order
+    segs, _ = layout.per_tensor_segments(numels, W, align)
+    for t, n in enumerate(numels):
+        mine = sorted((d, k) for tt, _s, d, k in segs if tt == t)
+        pos = 0
+        for d, k in mine:
+            assert d == pos and k > 0
+            pos += k
+        assert pos == n
+
+
+def test_per_tensor_divisible_case_is_a_reshape():
+    # when W divides every tensor the layout is numpy's reshape: a library routine
+    W = 8
+    numels = [64, 8 * 13, 8 * 512]
+    rng = np.random.default_rng(9)
+    tensors = [rng.integers(0, 1 << 16, size=n, dtype=np.uint16) for n in numels]
+    gathered = layout.per_tensor_gather(tensors, W, 1)
+    want = np.concatenate([t.reshape(W, -1) for t in tensors], axis=1).reshape(-1)
+    assert np.array_equal(gathered, want)
+    assert [s for s in layout.per_tensor_slices(numels, W)[0]] == [n // W for n in numels]
