@@ -276,6 +276,7 @@ def main():
 
     if not args.no_next_rows:
         result["next_rows"] = next_rows_leg(torch, synth, zc, dev)
+        result["next_rows"]["adaptive_offload_plan"] = adaptive_plan_leg(torch, zc, dev)
     if args.offload_elems > 0:
         legs = {}
         keep = zc.tune_get("offload.zero_copy")
@@ -334,6 +335,47 @@ def next_rows_leg(torch, synth, zc, dev):
                                "GBps": round(gb(4 * total) / (t_un * 1e-3), 1),
                                "frac": round(gb(4 * total) / (t_un * 1e-3) / HBM_PEAK_GBS, 4)},
     }
+
+
+def adaptive_plan_leg(torch, zc, dev):
+    """The paper's adaptive offloading (Algorithm 2 + backward reload) planned on a synthetic
+    memory profile (rising through the forward pass, falling through the backward pass) and
+    replayed with stand-in compute kernels: 32 optimizer-state fragments of 64 MiB, 24 of which
+    must leave, 16 + 16 operators of 8 ms.  Compared with offloading everything synchronously."""
+    nfrags, elems = 32, 16 << 20
+    state = torch.zeros(nfrags * elems, dtype=torch.float32, device=dev)
+    host = [zc.host_alloc(4 * elems) for _ in range(nfrags)]
+    frags = [(state[f * elems:(f + 1) * elems], host[f], 4 * elems) for f in range(nfrags)]
+    n_f = 16
+    up = [int(10 + 90 * (i + 1) / n_f) for i in range(n_f)]
+    p_mem = up + up[::-1]
+    ops = zc.plan_adaptive_offload(p_mem, n_f, [2] * nfrags, 116)
+    ops_all = ([(zc.OP_OFFLOAD, f) for f in range(nfrags)] + [(zc.OP_SYNC_FREE, f) for f in range(nfrags)]
+               + [(zc.OP_COMPUTE, i) for i in range(len(p_mem))]
+               + [(zc.OP_RELOAD, f) for f in range(nfrags)] + [(zc.OP_SYNC_RELOAD, f) for f in range(nfrags)])
+    ms = [8.0] * len(p_mem)
+    ctx = zc.offload_create(1 << 20, 2)
+
+    def run(sched):
+        ctx.schedule_run(sched, ms, frags, poison_freed=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.schedule_run(sched, ms, frags, poison_freed=True)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    t_none = run([(zc.OP_COMPUTE, i) for i in range(len(p_mem))])
+    t_adaptive = run(ops)
+    t_sync = run(ops_all)
+    ctx.destroy()
+    del state, frags
+    for h in host:
+        h.free()
+    moved = sum(1 for k, _ in ops if k == zc.OP_OFFLOAD)
+    return {"operators": len(p_mem), "operator_ms": 8.0, "fragments": nfrags, "fragment_MiB": 64,
+            "fragments_offloaded_by_plan": moved, "ms_no_offload": round(t_none, 1),
+            "ms_adaptive_plan": round(t_adaptive, 1), "ms_offload_all_sync": round(t_sync, 1),
+            "sync_over_adaptive": round(t_sync / t_adaptive, 3)}
 
 
 def offload_leg(torch, synth, zc, dev, args, probe=True):

@@ -209,6 +209,59 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
 zc_status zc_offload_destroy(zc_offload_ctx *ctx);
 
 /*
+ * Adaptive offloading of optimizer-state fragments (paper: Adaptive offloading,
+ * Algorithm 2, and the reload rule of the paragraph after it), as a host-only
+ * planner over a profiled schedule.
+ *   p_mem[i]      profiled memory in use before operator i, optimizer states not
+ *                 counted; operators [0, n_forward) are the forward pass, the
+ *                 rest the backward pass
+ *   frag_bytes[f] size of optimizer-state fragment f; their sum is M_opt
+ *   mem_limit     M
+ * Copies out are started at the very beginning for the shortest prefix of
+ * fragments that lets the largest p_mem fit; a fragment is waited for and freed
+ * (ZC_OP_SYNC_FREE) right before the first operator that needs its room; in the
+ * backward pass a copy back (ZC_OP_RELOAD) starts as soon as the largest p_mem
+ * from that operator to the end leaves room for it; every reload is waited for
+ * (ZC_OP_SYNC_RELOAD) at the end.  Fragments leave and return in list order.
+ * out receives at most `capacity` entries, *out_len the length of the schedule
+ * (n_ops + 4*nfrags always suffices).  ZC_ERR_UNSUPPORTED when an operator does
+ * not fit even with every fragment offloaded.  All pointers HOST.
+ */
+typedef enum {
+    ZC_OP_COMPUTE = 0,    /* index = operator */
+    ZC_OP_OFFLOAD = 1,    /* index = fragment: start the asynchronous copy to the host */
+    ZC_OP_SYNC_FREE = 2,  /* wait for that copy, then the device memory may be reused */
+    ZC_OP_RELOAD = 3,     /* start the asynchronous copy back */
+    ZC_OP_SYNC_RELOAD = 4 /* wait for the copy back */
+} zc_op_kind;
+typedef struct {
+    int32_t kind;
+    int32_t index;
+} zc_sched_op;
+zc_status zc_plan_adaptive_offload(const int64_t *p_mem, int64_t n_ops, int64_t n_forward,
+                                   const int64_t *frag_bytes, int64_t nfrags, int64_t mem_limit,
+                                   zc_sched_op *out, int64_t capacity, int64_t *out_len);
+
+/*
+ * Replay a schedule on HIP streams: operator i becomes a stand-in kernel that
+ * occupies `hip_stream` for op_ms[i] milliseconds (NULL = no kernels), copies run
+ * on the context's two copy streams, the wait operators become cross-stream event
+ * waits.  With poison_freed != 0 a freed fragment's device memory is overwritten,
+ * so a later use without reload shows.  The schedule is validated first
+ * (operators in order, each fragment offload -> free -> reload -> wait, all
+ * fragments back at the end).  frags[f].dev DEVICE, frags[f].host pinned HOST,
+ * bytes a multiple of 4.  Enqueues and returns.
+ */
+typedef struct {
+    void *dev;
+    void *host;
+    int64_t bytes;
+} zc_fragment;
+zc_status zc_schedule_run(zc_offload_ctx *ctx, const zc_sched_op *ops, int64_t nops,
+                          const float *op_ms, int64_t n_ops, const zc_fragment *frags,
+                          int64_t nfrags, int32_t poison_freed, void *hip_stream);
+
+/*
  * Pinned host memory of exactly `bytes` bytes for the offloaded partitions
  * (hipHostMalloc; page-locked, device-accessible, 4 KiB aligned).  A convenience
  * for callers whose allocator rounds pinned requests up (a 35 GB array then

@@ -35,7 +35,7 @@ struct Tune {
     int64_t adam_arith = 2;
     int64_t copy_waves_per_cu = 16;
     int64_t cast_waves_per_cu = 24;
-    int64_t accum_waves_per_cu = 16;
+    int64_t accum_waves_per_cu = 24;
     int64_t copy_nontemporal = 1;
     int64_t offload_zero_copy = 1;
     int64_t offload_zc_waves_per_cu = 0;

@@ -25,6 +25,7 @@
 // holds ~95 % of that ceiling every time, which is why it is the default.
 #include <chrono>
 #include <new>
+#include <vector>
 
 #include "zc_internal.h"
 
@@ -37,9 +38,12 @@ struct zc_offload_ctx {
     hipStream_t h2d = nullptr, d2h = nullptr;
     hipEvent_t entry = nullptr, done = nullptr;
     hipEvent_t loaded[8] = {}, updated[8] = {}, freed[8] = {};
+    std::vector<hipEvent_t> pool;  // extra events for schedule replay, grown on demand
 };
 
 namespace zc {
+
+hipStream_t offload_h2d_stream(zc_offload_ctx *ctx);
 
 static void destroy_ctx(zc_offload_ctx *c)
 {
@@ -58,10 +62,31 @@ static void destroy_ctx(zc_offload_ctx *c)
         if (c->updated[i]) (void)hipEventDestroy(c->updated[i]);
         if (c->freed[i]) (void)hipEventDestroy(c->freed[i]);
     }
+    for (hipEvent_t e : c->pool)
+        (void)hipEventDestroy(e);
     if (c->entry) (void)hipEventDestroy(c->entry);
     if (c->done) (void)hipEventDestroy(c->done);
     if (c->staging) (void)hipFree(c->staging);
     delete c;
+}
+
+hipStream_t offload_h2d_stream(zc_offload_ctx *ctx) { return ctx->h2d; }
+hipStream_t offload_d2h_stream(zc_offload_ctx *ctx) { return ctx->d2h; }
+int offload_device(zc_offload_ctx *ctx) { return ctx->device; }
+
+zc_status offload_events(zc_offload_ctx *ctx, int64_t count, hipEvent_t **out)
+{
+    try {
+        while ((int64_t)ctx->pool.size() < count) {
+            hipEvent_t e = nullptr;
+            ZC_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            ctx->pool.push_back(e);
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(ZC_ERR_NOMEM, "cannot grow the event pool");
+    }
+    *out = ctx->pool.data();
+    return ZC_OK;
 }
 
 // Pinned host memory is reported as hipMemoryTypeHost; pageable memory either

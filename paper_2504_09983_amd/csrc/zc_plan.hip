@@ -1,0 +1,262 @@
+// Adaptive offloading of optimizer-state fragments: the planner (host only) and a
+// small executor that replays a plan on HIP streams with stand-in compute kernels.
+//
+// Planner: forward pass as in the paper's Algorithm 2 (Adaptive offloading) —
+// start asynchronous copies of just enough fragments for the profiled peak to
+// fit, and insert "wait for the copy and free" right before the first operator
+// that would otherwise exceed the limit; backward pass as in the paragraph that
+// follows it — start the copy back of a fragment as soon as enough memory stays
+// free from that operator to the end of the schedule.  Fragments leave and
+// return in list order; every reload is waited for at the end, before the update.
+//
+// Executor: operators are spin kernels of given durations on the caller's
+// stream, copies run on the offload context's two copy streams, and the plan's
+// wait operators become cross-stream event waits, so the overlap the plan
+// promises can be measured against the "offload everything, synchronously" mode.
+#include <vector>
+
+#include "zc_internal.h"
+
+struct zc_offload_ctx;
+
+namespace zc {
+
+// Access to the copy streams of an offload context (defined with the context).
+hipStream_t offload_h2d_stream(zc_offload_ctx *ctx);
+hipStream_t offload_d2h_stream(zc_offload_ctx *ctx);
+int offload_device(zc_offload_ctx *ctx);
+zc_status offload_events(zc_offload_ctx *ctx, int64_t count, hipEvent_t **out);
+
+// Bounded busy-wait: leaves after `ticks` of the constant-rate wall clock or after
+// `max_iters` rounds, whichever comes first, so the wave always retires.
+__global__ __launch_bounds__(64) void spin_kernel(uint64_t ticks, int64_t max_iters)
+{
+    const uint64_t t0 = wall_clock64();
+    for (int64_t it = 0; it < max_iters; ++it) {
+        if (wall_clock64() - t0 >= ticks)
+            break;
+        __builtin_amdgcn_s_sleep(64);
+    }
+}
+
+__global__ __launch_bounds__(256) void poison_kernel(uint32_t *__restrict__ dst, int64_t nwords)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += stride)
+        dst[i] = 0xDEADBEEFu;
+}
+
+enum FragState { kResident, kCopyingOut, kOnHost, kCopyingIn };
+
+// Shared validation: the ordering rules any executable schedule must obey.
+static zc_status check_schedule(const zc_sched_op *ops, int64_t nops, int64_t n_ops, int64_t nfrags)
+{
+    std::vector<int> state((size_t)nfrags, kResident);
+    int64_t next_op = 0;
+    for (int64_t k = 0; k < nops; ++k) {
+        const int32_t kind = ops[k].kind, idx = ops[k].index;
+        if (kind == ZC_OP_COMPUTE) {
+            if (idx != next_op)
+                return fail(ZC_ERR_INVALID_ARG, "schedule entry %lld: operator %d out of order", (long long)k, idx);
+            ++next_op;
+            continue;
+        }
+        if (kind < ZC_OP_COMPUTE || kind > ZC_OP_SYNC_RELOAD)
+            return fail(ZC_ERR_INVALID_ARG, "schedule entry %lld: unknown kind %d", (long long)k, kind);
+        if (idx < 0 || idx >= nfrags)
+            return fail(ZC_ERR_INVALID_ARG, "schedule entry %lld: fragment %d out of range", (long long)k, idx);
+        int &s = state[(size_t)idx];
+        const int want = kind == ZC_OP_OFFLOAD ? kResident
+                         : kind == ZC_OP_SYNC_FREE ? kCopyingOut
+                         : kind == ZC_OP_RELOAD ? kOnHost : kCopyingIn;
+        if (s != want)
+            return fail(ZC_ERR_INVALID_ARG, "schedule entry %lld: fragment %d is in the wrong state for kind %d",
+                        (long long)k, idx, kind);
+        s = kind == ZC_OP_OFFLOAD ? kCopyingOut
+            : kind == ZC_OP_SYNC_FREE ? kOnHost
+            : kind == ZC_OP_RELOAD ? kCopyingIn : kResident;
+    }
+    if (next_op != n_ops)
+        return fail(ZC_ERR_INVALID_ARG, "schedule runs %lld of %lld operators", (long long)next_op, (long long)n_ops);
+    for (int64_t f = 0; f < nfrags; ++f)
+        if (state[(size_t)f] == kOnHost || state[(size_t)f] == kCopyingIn)
+            return fail(ZC_ERR_INVALID_ARG, "fragment %lld is not back on the device when the schedule ends", (long long)f);
+    return ZC_OK;
+}
+
+}  // namespace zc
+
+extern "C" {
+
+zc_status zc_plan_adaptive_offload(const int64_t *p_mem, int64_t n_ops, int64_t n_forward,
+                                   const int64_t *frag_bytes, int64_t nfrags, int64_t mem_limit,
+                                   zc_sched_op *out, int64_t capacity, int64_t *out_len)
+{
+    using namespace zc;
+    if (!out_len)
+        return fail(ZC_ERR_INVALID_ARG, "out_len is NULL");
+    *out_len = 0;
+    if (n_ops < 0 || n_forward < 0 || n_forward > n_ops || nfrags < 0 || mem_limit < 0)
+        return fail(ZC_ERR_INVALID_ARG, "need 0 <= n_forward <= n_ops, nfrags >= 0, mem_limit >= 0");
+    if ((n_ops > 0 && !p_mem) || (nfrags > 0 && !frag_bytes))
+        return fail(ZC_ERR_INVALID_ARG, "p_mem / frag_bytes is NULL");
+    if (n_ops > 0x7FFFFFFF || nfrags > 0x7FFFFFFF)
+        return fail(ZC_ERR_UNSUPPORTED, "more than 2^31 operators or fragments");
+    const int64_t kMax = int64_t(1) << 60;
+    int64_t m_opt = 0;
+    for (int64_t f = 0; f < nfrags; ++f) {
+        if (frag_bytes[f] < 0 || frag_bytes[f] > kMax - m_opt)
+            return fail(ZC_ERR_INVALID_ARG, "fragment sizes must be >= 0 and sum below 2^60");
+        m_opt += frag_bytes[f];
+    }
+    int64_t m_peak = 0;
+    for (int64_t i = 0; i < n_ops; ++i) {
+        if (p_mem[i] < 0 || p_mem[i] > kMax)
+            return fail(ZC_ERR_INVALID_ARG, "p_mem[%lld] out of range", (long long)i);
+        if (p_mem[i] > m_peak)
+            m_peak = p_mem[i];  // over the whole iteration: the spikes may sit in the backward pass
+    }
+
+    std::vector<zc_sched_op> s;
+    s.reserve((size_t)(n_ops + 4 * nfrags));
+    // Which fragments leave: the shortest prefix that lets the peak fit.
+    int64_t n_out = 0, out_bytes = 0;
+    while (n_out < nfrags && m_peak + m_opt - out_bytes > mem_limit) {
+        s.push_back({ZC_OP_OFFLOAD, (int32_t)n_out});
+        out_bytes += frag_bytes[n_out];
+        ++n_out;
+    }
+    // tail_max[i] = largest profiled usage from operator i to the end.
+    std::vector<int64_t> tail_max((size_t)n_ops + 1, 0);
+    for (int64_t i = n_ops - 1; i >= 0; --i)
+        tail_max[(size_t)i] = p_mem[i] > tail_max[(size_t)i + 1] ? p_mem[i] : tail_max[(size_t)i + 1];
+    // Fragments [0, freed) have been freed, [0, back) of those are on their way back.
+    int64_t freed = 0, back = 0, m_minus = 0;
+    for (int64_t i = 0; i < n_ops; ++i) {
+        // free a fragment (after waiting for its copy) only when an operator needs the room
+        while (p_mem[i] + m_opt - m_minus > mem_limit) {
+            if (freed == n_out)
+                return fail(ZC_ERR_UNSUPPORTED,
+                            "operator %lld needs %lld bytes: over the limit even with every fragment offloaded",
+                            (long long)i, (long long)p_mem[i]);
+            s.push_back({ZC_OP_SYNC_FREE, (int32_t)freed});
+            m_minus += frag_bytes[freed];
+            ++freed;
+        }
+        // backward pass: start a copy back as soon as the rest of the schedule leaves room
+        if (i >= n_forward) {
+            while (back < freed && tail_max[(size_t)i] + m_opt - m_minus + frag_bytes[back] <= mem_limit) {
+                s.push_back({ZC_OP_RELOAD, (int32_t)back});
+                m_minus -= frag_bytes[back];
+                ++back;
+            }
+        }
+        s.push_back({ZC_OP_COMPUTE, (int32_t)i});
+    }
+    for (; back < freed; ++back)
+        s.push_back({ZC_OP_RELOAD, (int32_t)back});
+    for (int64_t f = 0; f < freed; ++f)
+        s.push_back({ZC_OP_SYNC_RELOAD, (int32_t)f});
+
+    *out_len = (int64_t)s.size();
+    if ((int64_t)s.size() > capacity || (!out && !s.empty()))
+        return fail(ZC_ERR_INVALID_ARG, "schedule has %lld entries, room for %lld", (long long)s.size(),
+                    (long long)capacity);
+    for (size_t k = 0; k < s.size(); ++k)
+        out[k] = s[k];
+    return ZC_OK;
+}
+
+zc_status zc_schedule_run(zc_offload_ctx *ctx, const zc_sched_op *ops, int64_t nops, const float *op_ms,
+                          int64_t n_ops, const zc_fragment *frags, int64_t nfrags, int32_t poison_freed,
+                          void *hip_stream)
+{
+    using namespace zc;
+    if (!ctx)
+        return fail(ZC_ERR_INVALID_ARG, "ctx is NULL");
+    if (nops < 0 || n_ops < 0 || nfrags < 0)
+        return fail(ZC_ERR_INVALID_ARG, "negative count");
+    if ((nops > 0 && !ops) || (nfrags > 0 && !frags))
+        return fail(ZC_ERR_INVALID_ARG, "ops / frags is NULL");
+    ZC_TRY(check_schedule(ops, nops, n_ops, nfrags));
+    for (int64_t i = 0; op_ms && i < n_ops; ++i)
+        if (!(op_ms[i] >= 0.0f && op_ms[i] <= 10000.0f))
+            return fail(ZC_ERR_INVALID_ARG, "op_ms[%lld] must be in [0, 10000]", (long long)i);
+    for (int64_t f = 0; f < nfrags; ++f) {
+        if (frags[f].bytes < 0 || (frags[f].bytes > 0 && (!frags[f].dev || !frags[f].host)))
+            return fail(ZC_ERR_INVALID_ARG, "fragment %lld: bad size or NULL pointer", (long long)f);
+        if (frags[f].bytes % 4 != 0 || !aligned_to(frags[f].dev, 4))
+            return fail(ZC_ERR_ALIGNMENT, "fragment %lld: size and device pointer must be multiples of 4",
+                        (long long)f);
+    }
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev != offload_device(ctx))
+        return fail(ZC_ERR_INVALID_ARG, "context belongs to another device");
+    int clock_khz = 0;
+    ZC_HIP(hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev));
+    if (clock_khz <= 0)
+        clock_khz = 100000;
+    int cus = 0;
+    ZC_TRY(num_cus(&cus));
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipStream_t h2d = offload_h2d_stream(ctx), d2h = offload_d2h_stream(ctx);
+    // events: [0, nfrags) copy-out done, [nfrags, 2 nfrags) copy-in done, then one marker per copy start
+    hipEvent_t *ev = nullptr;
+    ZC_TRY(offload_events(ctx, 4 * nfrags, &ev));
+
+    for (int64_t k = 0; k < nops; ++k) {
+        const int32_t kind = ops[k].kind, idx = ops[k].index;
+        switch (kind) {
+        case ZC_OP_COMPUTE: {
+            const double ms = op_ms ? (double)op_ms[idx] : 0.0;
+            if (ms > 0.0) {
+                const uint64_t ticks = (uint64_t)(ms * (double)clock_khz);
+                const int64_t max_iters = (int64_t)(ms * 20000.0) + 1000;
+                hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, stream, ticks, max_iters);
+                ZC_HIP(hipGetLastError());
+            }
+            break;
+        }
+        case ZC_OP_OFFLOAD:
+            // the copy may start once the caller's stream has reached this point of the schedule
+            ZC_HIP(hipEventRecord(ev[2 * nfrags + idx], stream));
+            ZC_HIP(hipStreamWaitEvent(d2h, ev[2 * nfrags + idx], 0));
+            if (frags[idx].bytes > 0)
+                ZC_HIP(hipMemcpyAsync(frags[idx].host, frags[idx].dev, (size_t)frags[idx].bytes,
+                                      hipMemcpyDeviceToHost, d2h));
+            ZC_HIP(hipEventRecord(ev[idx], d2h));
+            break;
+        case ZC_OP_SYNC_FREE:
+            ZC_HIP(hipStreamWaitEvent(stream, ev[idx], 0));
+            if (poison_freed && frags[idx].bytes > 0) {
+                // stands in for handing the memory to someone else
+                const int64_t words = frags[idx].bytes / 4;
+                int64_t blocks = (words + 255) / 256;
+                if (blocks > (int64_t)cus * 8)
+                    blocks = (int64_t)cus * 8;
+                hipLaunchKernelGGL(poison_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                                   static_cast<uint32_t *>(frags[idx].dev), words);
+                ZC_HIP(hipGetLastError());
+            }
+            break;
+        case ZC_OP_RELOAD:
+            ZC_HIP(hipEventRecord(ev[3 * nfrags + idx], stream));
+            ZC_HIP(hipStreamWaitEvent(h2d, ev[3 * nfrags + idx], 0));
+            if (frags[idx].bytes > 0)
+                ZC_HIP(hipMemcpyAsync(frags[idx].dev, frags[idx].host, (size_t)frags[idx].bytes,
+                                      hipMemcpyHostToDevice, h2d));
+            ZC_HIP(hipEventRecord(ev[nfrags + idx], h2d));
+            break;
+        case ZC_OP_SYNC_RELOAD:
+            ZC_HIP(hipStreamWaitEvent(stream, ev[nfrags + idx], 0));
+            break;
+        default:
+            break;
+        }
+    }
+    return ZC_OK;
+}
+
+}  // extern "C"

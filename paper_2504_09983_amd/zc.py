@@ -37,6 +37,17 @@ class AdamHparams(ctypes.Structure):
                 ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
+class SchedOp(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("index", ctypes.c_int32)]
+
+
+class Fragment(ctypes.Structure):
+    _fields_ = [("dev", ctypes.c_void_p), ("host", ctypes.c_void_p), ("bytes", ctypes.c_int64)]
+
+
+OP_COMPUTE, OP_OFFLOAD, OP_SYNC_FREE, OP_RELOAD, OP_SYNC_RELOAD = range(5)
+
+
 class Segment(ctypes.Structure):
     _fields_ = [("src_offset", ctypes.c_int64), ("dst", ctypes.c_void_p),
                 ("numel", ctypes.c_int64)]
@@ -87,6 +98,12 @@ def lib():
                                        ctypes.POINTER(AdamHparams), vp, vp, vp]
     L.zc_offload_destroy.restype = ctypes.c_int
     L.zc_offload_destroy.argtypes = [vp]
+    L.zc_plan_adaptive_offload.restype = ctypes.c_int
+    L.zc_plan_adaptive_offload.argtypes = [ctypes.POINTER(i64), i64, i64, ctypes.POINTER(i64), i64, i64,
+                                           ctypes.POINTER(SchedOp), i64, ctypes.POINTER(i64)]
+    L.zc_schedule_run.restype = ctypes.c_int
+    L.zc_schedule_run.argtypes = [vp, ctypes.POINTER(SchedOp), i64, ctypes.POINTER(ctypes.c_float), i64,
+                                  ctypes.POINTER(Fragment), i64, i32, vp]
     L.zc_host_alloc.restype = ctypes.c_int
     L.zc_host_alloc.argtypes = [i64, ctypes.POINTER(vp)]
     L.zc_host_free.restype = ctypes.c_int
@@ -180,6 +197,20 @@ def per_tensor_layout(numels: Sequence[int], world: int, align: int = 1):
     return segs, send.value
 
 
+def plan_adaptive_offload(p_mem: Sequence[int], n_forward: int, frag_bytes: Sequence[int],
+                          mem_limit: int):
+    """Schedule as a list of (kind, index) from the C planner."""
+    n, k = len(p_mem), len(frag_bytes)
+    pm = (ctypes.c_int64 * max(1, n))(*[int(x) for x in p_mem])
+    fb = (ctypes.c_int64 * max(1, k))(*[int(x) for x in frag_bytes])
+    cap = n + 4 * k
+    out = (SchedOp * max(1, cap))()
+    length = ctypes.c_int64(0)
+    _check(lib().zc_plan_adaptive_offload(pm, n, n_forward, fb, k, mem_limit, out, cap,
+                                          ctypes.byref(length)))
+    return [(out[i].kind, out[i].index) for i in range(length.value)]
+
+
 class UnshardPlan:
     """Owns a zc_unshard_plan; segments are (src_offset, dst address or tensor, numel)."""
 
@@ -230,6 +261,20 @@ class OffloadCtx:
                                           n_resident, _addr(p_host), _addr(m_host), _addr(v_host),
                                           n_streamed, _addr(g_dev), g_dtype, ctypes.byref(hp),
                                           _addr(bf16_out_dev), _addr(skip_flag), _stream(stream)))
+
+    def schedule_run(self, ops, op_ms, fragments, poison_freed: bool = False, stream=None) -> None:
+        """Replay a schedule: ops = [(kind, index)], op_ms = per-operator milliseconds or None,
+        fragments = [(device tensor/address, pinned host address, bytes)]."""
+        arr = (SchedOp * max(1, len(ops)))(*[SchedOp(int(k), int(i)) for k, i in ops])
+        n_ops = sum(1 for k, _ in ops if k == OP_COMPUTE)
+        ms = None
+        if op_ms is not None:
+            ms = (ctypes.c_float * max(1, len(op_ms)))(*[float(x) for x in op_ms])
+            n_ops = len(op_ms)
+        fr = (Fragment * max(1, len(fragments)))(*[Fragment(_addr(d), _addr(h), int(b))
+                                                   for d, h, b in fragments])
+        _check(lib().zc_schedule_run(self._h, arr, len(ops), ms, n_ops, fr, len(fragments),
+                                     1 if poison_freed else 0, _stream(stream)))
 
     def probe_link(self, host_src, host_dst, nbytes: int, mode: int) -> float:
         """Wall milliseconds of plain chunked pinned copies (0 = H2D, 1 = D2H, 2 = both)."""

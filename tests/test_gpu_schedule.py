@@ -1,0 +1,139 @@
+"""GPU: replaying an adaptive-offloading plan.  Data integrity (every fragment is back,
+bit for bit, although its device memory was overwritten after the free), the optimizer
+step after the replay equals the never-offloaded step, bad schedules are refused, and the
+planned overlap is faster than offloading everything synchronously."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import planner as P
+from paper_2504_09983_amd import synth, zc
+from tests.gpu_util import DEV, HP, dev_f32, host_f32, sync
+
+pytestmark = pytest.mark.gpu
+
+
+def make_fragments(nfrags, elems, seed):
+    """m and v style state cut into fragments: device tensors + pinned host mirrors."""
+    state = dev_f32(np.abs(synth.host_normal(nfrags * elems, 1e-3, seed)))
+    host = [zc.host_alloc(4 * elems) for _ in range(nfrags)]
+    frags = [(state[f * elems:(f + 1) * elems], host[f], 4 * elems) for f in range(nfrags)]
+    return state, host, frags
+
+
+def test_replay_keeps_every_bit_and_the_step_is_unchanged():
+    nfrags, elems = 6, 1 << 16
+    n = nfrags * elems
+    m, m_host, m_frags = make_fragments(nfrags, elems, 81)
+    m0 = m.clone()
+    p_mem = [10, 30, 60, 90, 70, 40, 20]
+    frag_cost = [10] * nfrags
+    ops = zc.plan_adaptive_offload(p_mem, 4, frag_cost, 120)
+    assert ops == P.plan(p_mem, 4, frag_cost, 120)
+    assert sum(1 for k, _ in ops if k == zc.OP_SYNC_FREE) == 3
+    ctx = zc.offload_create(1 << 20, 2)
+    ctx.schedule_run(ops, [0.2] * len(p_mem), m_frags, poison_freed=True)
+    sync()
+    assert torch.equal(m, m0)
+    # host mirrors of the freed fragments hold the data, the others were never written
+    for f in range(3):
+        assert np.array_equal(m_host[f].numpy("float32"), host_f32(m0[f * elems:(f + 1) * elems]))
+    # the offload-all mode moves everything out and back
+    ops_all = P.plan_offload_all_sync(len(p_mem), nfrags)
+    ctx.schedule_run(ops_all, None, m_frags, poison_freed=True)
+    sync()
+    assert torch.equal(m, m0)
+    # the parameter update after the replay equals the update without any offloading
+    p = synth.host_params(n, 82)
+    g = synth.host_grads_f32(n, 1)
+    a = [dev_f32(p), m0.clone(), dev_f32(np.abs(synth.host_normal(n, 1e-7, 83)))]
+    b = [a[0].clone(), m, a[2].clone()]
+    dg = dev_f32(g)
+    zc.adam_step(*a, dg, zc.F32, n, zc.hparams(step=3, **HP))
+    zc.adam_step(*b, dg, zc.F32, n, zc.hparams(step=3, **HP))
+    sync()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    ctx.destroy()
+    for h in m_host:
+        h.free()
+
+
+def test_poison_shows_a_missing_reload():
+    """Sanity of the check itself: without the reload the data is gone."""
+    nfrags, elems = 2, 4096
+    m, m_host, m_frags = make_fragments(nfrags, elems, 84)
+    m0 = m.clone()
+    ctx = zc.offload_create(1 << 16, 2)
+    # fragment 0 leaves and returns; fragment 1's copy is started but its memory is kept
+    ops = [(zc.OP_OFFLOAD, 0), (zc.OP_OFFLOAD, 1), (zc.OP_SYNC_FREE, 0), (zc.OP_COMPUTE, 0),
+           (zc.OP_RELOAD, 0), (zc.OP_SYNC_RELOAD, 0)]
+    ctx.schedule_run(ops, [0.1], m_frags, poison_freed=True)
+    sync()
+    assert torch.equal(m, m0)
+    # a schedule that frees without ever reloading is refused before anything runs
+    bad = [(zc.OP_OFFLOAD, 0), (zc.OP_SYNC_FREE, 0), (zc.OP_COMPUTE, 0)]
+    for sched in (bad, [(zc.OP_SYNC_FREE, 0), (zc.OP_COMPUTE, 0)], [(zc.OP_COMPUTE, 1)],
+                  [(zc.OP_RELOAD, 0), (zc.OP_COMPUTE, 0)], [(zc.OP_OFFLOAD, 5), (zc.OP_COMPUTE, 0)]):
+        with pytest.raises(zc.ZcError) as ei:
+            ctx.schedule_run(sched, [0.1], m_frags, poison_freed=True)
+        assert ei.value.status == zc.ERR_INVALID_ARG
+    sync()
+    assert torch.equal(m, m0)
+    ctx.destroy()
+    for h in m_host:
+        h.free()
+
+
+def test_spin_kernel_durations_are_honoured():
+    ctx = zc.offload_create(1 << 16, 2)
+    ops = [(zc.OP_COMPUTE, i) for i in range(10)]
+    ctx.schedule_run(ops, [1.0] * 10, [])       # warm-up
+    sync()
+    t0 = time.perf_counter()
+    ctx.schedule_run(ops, [5.0] * 10, [])
+    sync()
+    dt = (time.perf_counter() - t0) * 1e3
+    assert 48.0 <= dt <= 80.0, dt
+    ctx.destroy()
+
+
+def test_planned_overlap_beats_offload_all_sync():
+    """32 fragments of 64 MiB; 16 forward + 16 backward operators of 8 ms; the limit forces
+    three quarters of the state out.  The copies (1.5 GiB each way) hide behind compute in the
+    adaptive plan and are fully exposed in the synchronous mode."""
+    nfrags, elems = 32, 16 << 20
+    m, m_host, m_frags = make_fragments(nfrags, elems, 85)
+    m0 = m.clone()
+    n_f = n_b = 16
+    up = [int(10 + 90 * (i + 1) / n_f) for i in range(n_f)]
+    p_mem = up + up[::-1]
+    cost = [2] * nfrags                       # M_opt = 64
+    M = 100 + 16                              # peak 100 + 64 - 48 = 116: 24 fragments leave
+    ops = zc.plan_adaptive_offload(p_mem, n_f, cost, M)
+    assert sum(1 for k, _ in ops if k == zc.OP_OFFLOAD) == 24
+    ops_all = P.plan_offload_all_sync(len(p_mem), nfrags)
+    ms = [8.0] * len(p_mem)
+    ctx = zc.offload_create(1 << 20, 2)
+
+    def run(sched):
+        ctx.schedule_run(sched, ms, m_frags, poison_freed=True)
+        sync()
+        t0 = time.perf_counter()
+        ctx.schedule_run(sched, ms, m_frags, poison_freed=True)
+        sync()
+        return (time.perf_counter() - t0) * 1e3
+
+    t_none = run([(zc.OP_COMPUTE, i) for i in range(len(p_mem))])
+    t_adaptive = run(ops)
+    t_sync = run(ops_all)
+    print(f"no offload {t_none:.1f} ms, adaptive {t_adaptive:.1f} ms, offload-all+sync {t_sync:.1f} ms")
+    assert torch.equal(m, m0)
+    assert t_adaptive < t_sync * 0.9
+    assert t_adaptive < t_none * 1.15
+    ctx.destroy()
+    for h in m_host:
+        h.free()
