@@ -243,6 +243,40 @@ zc_status zc_plan_adaptive_offload(const int64_t *p_mem, int64_t n_ops, int64_t 
                                    zc_sched_op *out, int64_t capacity, int64_t *out_len);
 
 /*
+ * Proactive prefetching (paper: Proactive prefetching, Algorithm 1) with Fuse, as a
+ * host-only planner.  The schedule o_0..o_{n-1} is walked from the back; an
+ * all-gather keeps moving towards the front together with the other unscheduled
+ * ones while the profiled memory before its predecessor plus their buffers stays
+ * below mem_limit and their total stays below prefetch_limit; when that fails the
+ * group is placed and the all-gather opens the next group if it fits alone, else
+ * it stays where it is.  A placed group is fused pairwise in schedule order while
+ * T_c(V1) + T_c(V2) > alpha * T_c(V1 + V2), T_c being the profiled table
+ * (tc_sizes increasing, tc_times; linear between samples, flat below the first,
+ * last slope beyond the last).
+ *   is_allgather[i], bag_bytes[i] (B_ag, > 0 for all-gathers), p_mem[i] (P_mem)
+ *   order_out[k]   operator at position k of the new schedule
+ *   group_out[k]   -1 for other operators; all-gathers with equal ids are fused
+ * All pointers HOST, tables of n_ops entries.
+ */
+zc_status zc_plan_prefetch(const int32_t *is_allgather, const int64_t *bag_bytes,
+                           const int64_t *p_mem, int64_t n_ops, int64_t mem_limit,
+                           int64_t prefetch_limit, const int64_t *tc_sizes,
+                           const double *tc_times, int64_t n_tc, double alpha,
+                           int32_t *order_out, int32_t *group_out);
+
+/*
+ * Selective unsharding (paper: Selective unsharding): which gathered parameters to
+ * keep unsharded until the update, within `budget` bytes of memory left after
+ * prefetching.  Parameters are taken in order of communication time saved per byte,
+ * T_c(B_ag)/B_ag, highest first (smaller buffers first among equals), each one that
+ * still fits.  chosen_out receives the indices in the order chosen (room for n),
+ * *n_chosen_out their count.  All pointers HOST.
+ */
+zc_status zc_select_unsharded(const int64_t *bag_bytes, int64_t n, const int64_t *tc_sizes,
+                              const double *tc_times, int64_t n_tc, int64_t budget,
+                              int32_t *chosen_out, int64_t *n_chosen_out);
+
+/*
  * Replay a schedule on HIP streams: operator i becomes a stand-in kernel that
  * occupies `hip_stream` for op_ms[i] milliseconds (NULL = no kernels), copies run
  * on the context's two copy streams, the wait operators become cross-stream event

@@ -107,3 +107,100 @@ def peak_memory(S, p_mem, frag_bytes):
             peak = max(peak, p_mem[idx] + resident)
     assert all(s in ("resident", "copying_out") for s in state), "a fragment is missing at the update"
     return peak
+
+
+# ---------------------------------------------------------------------------
+# Proactive prefetching (Algorithm 1), Fuse, and the selective-unsharding choice.
+#
+# Notation as in the paper's Table 1: S0 initial schedule o_1..o_N, M memory
+# limit, M_prefetch limit of a prefetch group, P_mem(o), B_ag(o), Fuse(U),
+# T_c(V), alpha.
+#
+# Readings where the listing is incomplete: (1) in the branch where o_i does not
+# fit, the group U is flushed and o_i then opens the next group if it fits on
+# its own, otherwise it stays where it is; (2) o_1 has no predecessor to test
+# against: an all-gather there joins the last group unless the group limit says no; (3) S is assembled back to
+# front and reversed at the end; (4) Fuse walks the group in schedule order and
+# merges the next all-gather into the current fused one while
+# T_c(V1) + T_c(V2) > alpha * T_c(V1 + V2); (5) T_c(V) is the profiled table,
+# linear between samples, flat below the first and continued with the last slope.
+# ---------------------------------------------------------------------------
+
+def t_c(V, sizes, times):
+    """Profiled communication time for V bytes from the (sizes, times) table."""
+    if V <= sizes[0]:
+        return times[0]
+    k = len(sizes) - 1
+    for i in range(1, len(sizes)):
+        if V <= sizes[i]:
+            k = i
+            break
+    s0, s1, t0, t1 = sizes[k - 1], sizes[k], times[k - 1], times[k]
+    return t0 + (t1 - t0) * (V - s0) / (s1 - s0)
+
+
+def fuse(U, bag, sizes, times, alpha):
+    """Fuse(U): list of groups (lists of operator indices) in schedule order."""
+    groups = []
+    for o in U:
+        if groups:
+            V1 = sum(bag[x] for x in groups[-1])
+            V2 = bag[o]
+            if t_c(V1, sizes, times) + t_c(V2, sizes, times) > alpha * t_c(V1 + V2, sizes, times):
+                groups[-1].append(o)
+                continue
+        groups.append([o])
+    return groups
+
+
+def plan_prefetch(is_ag, bag, p_mem, M, M_prefetch, sizes, times, alpha):
+    """Algorithm 1.  Returns the new schedule as a list of entries, each either
+    ("op", i) or ("allgather", [i, j, ...]) for a fused group."""
+    N = len(is_ag)
+    S = []          # built back to front
+    U = []          # unscheduled all-gathers, latest first
+
+    def flush():
+        if U:
+            for grp in reversed(fuse(list(reversed(U)), bag, sizes, times, alpha)):
+                S.append(("allgather", grp))
+            U.clear()
+
+    for i in range(N - 1, 0, -1):           # o_N ... o_2 (0-based N-1 ... 1)
+        if is_ag[i]:
+            m_U = sum(bag[o] for o in U) + bag[i]
+            m_prev = p_mem[i - 1] + m_U
+            if m_prev < M and m_U < M_prefetch:
+                U.append(i)
+            else:
+                flush()
+                if p_mem[i - 1] + bag[i] < M and bag[i] < M_prefetch:
+                    U.append(i)
+                else:
+                    S.append(("allgather", [i]))
+        else:
+            S.append(("op", i))
+    if N:
+        if is_ag[0]:
+            if sum(bag[o] for o in U) + bag[0] >= M_prefetch:
+                flush()
+            U.append(0)
+        else:
+            flush()
+            S.append(("op", 0))
+    flush()
+    S.reverse()
+    return S
+
+
+def select_unsharded(bag, sizes, times, budget):
+    """Selective unsharding: keep as many parameters gathered as fit in `budget`,
+    in order of communication time saved per byte, T_c(B_ag) / B_ag (smaller
+    buffers first among equals).  Returns the chosen indices in the order chosen."""
+    order = sorted(range(len(bag)), key=lambda o: (-t_c(bag[o], sizes, times) / bag[o], bag[o], o))
+    chosen, used = [], 0
+    for o in order:
+        if used + bag[o] <= budget:
+            chosen.append(o)
+            used += bag[o]
+    return chosen

@@ -13,6 +13,7 @@
 // stream, copies run on the offload context's two copy streams, and the plan's
 // wait operators become cross-stream event waits, so the overlap the plan
 // promises can be measured against the "offload everything, synchronously" mode.
+#include <algorithm>
 #include <vector>
 
 #include "zc_internal.h"
@@ -44,6 +45,35 @@ __global__ __launch_bounds__(256) void poison_kernel(uint32_t *__restrict__ dst,
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += stride)
         dst[i] = 0xDEADBEEFu;
+}
+
+// Profiled communication time for `bytes`: the table is linear between samples, flat
+// below the first one and continued with the last slope above the last one.
+static double comm_time(int64_t bytes, const int64_t *sizes, const double *times, int64_t n)
+{
+    if (bytes <= sizes[0] || n == 1)
+        return times[0];
+    int64_t k = n - 1;
+    for (int64_t i = 1; i < n; ++i) {
+        if (bytes <= sizes[i]) {
+            k = i;
+            break;
+        }
+    }
+    const double s0 = (double)sizes[k - 1], s1 = (double)sizes[k];
+    const double t0 = times[k - 1], t1 = times[k];
+    return t0 + (t1 - t0) * ((double)bytes - s0) / (s1 - s0);
+}
+
+static zc_status check_comm_table(const int64_t *sizes, const double *times, int64_t n)
+{
+    if (n < 1 || !sizes || !times)
+        return fail(ZC_ERR_INVALID_ARG, "the communication-time table needs at least one sample");
+    for (int64_t i = 0; i < n; ++i) {
+        if (sizes[i] <= 0 || !(times[i] >= 0.0) || (i > 0 && sizes[i] <= sizes[i - 1]))
+            return fail(ZC_ERR_INVALID_ARG, "table sizes must be positive and increasing, times >= 0");
+    }
+    return ZC_OK;
 }
 
 enum FragState { kResident, kCopyingOut, kOnHost, kCopyingIn };
@@ -164,6 +194,161 @@ zc_status zc_plan_adaptive_offload(const int64_t *p_mem, int64_t n_ops, int64_t 
                     (long long)capacity);
     for (size_t k = 0; k < s.size(); ++k)
         out[k] = s[k];
+    return ZC_OK;
+}
+
+zc_status zc_plan_prefetch(const int32_t *is_allgather, const int64_t *bag_bytes, const int64_t *p_mem,
+                           int64_t n_ops, int64_t mem_limit, int64_t prefetch_limit,
+                           const int64_t *tc_sizes, const double *tc_times, int64_t n_tc, double alpha,
+                           int32_t *order_out, int32_t *group_out)
+{
+    using namespace zc;
+    if (n_ops < 0 || mem_limit < 0 || prefetch_limit < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n_ops, mem_limit and prefetch_limit must be >= 0");
+    if (n_ops > 0 && (!is_allgather || !bag_bytes || !p_mem || !order_out || !group_out))
+        return fail(ZC_ERR_INVALID_ARG, "an input or output table is NULL");
+    if (n_ops > 0x7FFFFFFF)
+        return fail(ZC_ERR_UNSUPPORTED, "more than 2^31 operators");
+    if (!(alpha >= 0.0))
+        return fail(ZC_ERR_INVALID_ARG, "alpha must be >= 0");
+    ZC_TRY(check_comm_table(tc_sizes, tc_times, n_tc));
+    const int64_t kMax = int64_t(1) << 60;
+    for (int64_t i = 0; i < n_ops; ++i) {
+        if (p_mem[i] < 0 || p_mem[i] > kMax || bag_bytes[i] < 0 || bag_bytes[i] > kMax)
+            return fail(ZC_ERR_INVALID_ARG, "operator %lld: sizes out of range", (long long)i);
+        if (is_allgather[i] && bag_bytes[i] == 0)
+            return fail(ZC_ERR_INVALID_ARG, "operator %lld: an all-gather needs a buffer size", (long long)i);
+    }
+
+    // The new schedule is assembled back to front: (operator, group id) pairs.
+    std::vector<int32_t> rev_op, rev_grp;
+    rev_op.reserve((size_t)n_ops);
+    rev_grp.reserve((size_t)n_ops);
+    std::vector<int32_t> pending;  // unscheduled all-gathers, latest first
+    int64_t pending_bytes = 0;
+    int32_t next_group = 0;
+
+    // Place the pending all-gathers here, fused where two of them together are cheaper than
+    // apart by the factor alpha.  Groups are formed in schedule order (earliest first).
+    auto flush = [&]() {
+        if (pending.empty())
+            return;
+        std::vector<int32_t> grp_of(pending.size());
+        int64_t cur_bytes = 0;
+        int32_t cur = -1;
+        for (size_t k = pending.size(); k-- > 0;) {  // earliest first
+            const int64_t v2 = bag_bytes[pending[k]];
+            bool join = false;
+            if (cur >= 0) {
+                const double apart = comm_time(cur_bytes, tc_sizes, tc_times, n_tc) +
+                                     comm_time(v2, tc_sizes, tc_times, n_tc);
+                join = apart > alpha * comm_time(cur_bytes + v2, tc_sizes, tc_times, n_tc);
+            }
+            if (join) {
+                cur_bytes += v2;
+            } else {
+                cur = next_group++;
+                cur_bytes = v2;
+            }
+            grp_of[k] = cur;
+        }
+        for (size_t k = 0; k < pending.size(); ++k) {  // latest first, as the list is reversed later
+            rev_op.push_back(pending[k]);
+            rev_grp.push_back(grp_of[k]);
+        }
+        pending.clear();
+        pending_bytes = 0;
+    };
+
+    for (int64_t i = n_ops - 1; i >= 1; --i) {
+        if (!is_allgather[i]) {
+            rev_op.push_back((int32_t)i);
+            rev_grp.push_back(-1);
+            continue;
+        }
+        const int64_t group_bytes = pending_bytes + bag_bytes[i];
+        if (p_mem[i - 1] + group_bytes < mem_limit && group_bytes < prefetch_limit) {
+            pending.push_back((int32_t)i);  // moves further up together with the others
+            pending_bytes = group_bytes;
+        } else {
+            flush();
+            if (p_mem[i - 1] + bag_bytes[i] < mem_limit && bag_bytes[i] < prefetch_limit) {
+                pending.push_back((int32_t)i);
+                pending_bytes = bag_bytes[i];
+            } else {
+                rev_op.push_back((int32_t)i);  // stays where it is
+                rev_grp.push_back(next_group++);
+            }
+        }
+    }
+    if (n_ops > 0) {
+        if (is_allgather[0]) {
+            if (pending_bytes + bag_bytes[0] >= prefetch_limit)
+                flush();
+            pending.push_back(0);
+            pending_bytes += bag_bytes[0];
+        } else {
+            flush();
+            rev_op.push_back(0);
+            rev_grp.push_back(-1);
+        }
+    }
+    flush();
+    // Reverse, renumbering the groups in schedule order.
+    std::vector<int32_t> renumber((size_t)next_group, -1);
+    int32_t seen = 0;
+    for (int64_t k = 0; k < n_ops; ++k) {
+        const size_t r = (size_t)(n_ops - 1 - k);
+        order_out[k] = rev_op[r];
+        int32_t g = rev_grp[r];
+        if (g >= 0) {
+            if (renumber[(size_t)g] < 0)
+                renumber[(size_t)g] = seen++;
+            g = renumber[(size_t)g];
+        }
+        group_out[k] = g;
+    }
+    return ZC_OK;
+}
+
+zc_status zc_select_unsharded(const int64_t *bag_bytes, int64_t n, const int64_t *tc_sizes,
+                              const double *tc_times, int64_t n_tc, int64_t budget, int32_t *chosen_out,
+                              int64_t *n_chosen_out)
+{
+    using namespace zc;
+    if (n < 0 || budget < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n and budget must be >= 0");
+    if (!n_chosen_out || (n > 0 && (!bag_bytes || !chosen_out)))
+        return fail(ZC_ERR_INVALID_ARG, "an input or output table is NULL");
+    if (n > 0x7FFFFFFF)
+        return fail(ZC_ERR_UNSUPPORTED, "more than 2^31 parameters");
+    ZC_TRY(check_comm_table(tc_sizes, tc_times, n_tc));
+    for (int64_t i = 0; i < n; ++i)
+        if (bag_bytes[i] <= 0)
+            return fail(ZC_ERR_INVALID_ARG, "bag_bytes[%lld] must be positive", (long long)i);
+    std::vector<int32_t> order((size_t)n);
+    std::vector<double> ratio((size_t)n);
+    for (int64_t i = 0; i < n; ++i) {
+        order[(size_t)i] = (int32_t)i;
+        ratio[(size_t)i] = comm_time(bag_bytes[i], tc_sizes, tc_times, n_tc) / (double)bag_bytes[i];
+    }
+    // most communication time saved per byte first; smaller buffers, then earlier ones, among equals
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (ratio[(size_t)a] != ratio[(size_t)b])
+            return ratio[(size_t)a] > ratio[(size_t)b];
+        if (bag_bytes[a] != bag_bytes[b])
+            return bag_bytes[a] < bag_bytes[b];
+        return a < b;
+    });
+    int64_t used = 0, count = 0;
+    for (int64_t k = 0; k < n; ++k) {
+        const int32_t o = order[(size_t)k];
+        if (bag_bytes[o] <= budget - used) {
+            chosen_out[count++] = o;
+            used += bag_bytes[o];
+        }
+    }
+    *n_chosen_out = count;
     return ZC_OK;
 }
 

@@ -101,6 +101,14 @@ def lib():
     L.zc_plan_adaptive_offload.restype = ctypes.c_int
     L.zc_plan_adaptive_offload.argtypes = [ctypes.POINTER(i64), i64, i64, ctypes.POINTER(i64), i64, i64,
                                            ctypes.POINTER(SchedOp), i64, ctypes.POINTER(i64)]
+    dbl = ctypes.c_double
+    L.zc_plan_prefetch.restype = ctypes.c_int
+    L.zc_plan_prefetch.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(i64), i64, i64,
+                                   i64, ctypes.POINTER(i64), ctypes.POINTER(dbl), i64, dbl,
+                                   ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.zc_select_unsharded.restype = ctypes.c_int
+    L.zc_select_unsharded.argtypes = [ctypes.POINTER(i64), i64, ctypes.POINTER(i64), ctypes.POINTER(dbl),
+                                      i64, i64, ctypes.POINTER(i32), ctypes.POINTER(i64)]
     L.zc_schedule_run.restype = ctypes.c_int
     L.zc_schedule_run.argtypes = [vp, ctypes.POINTER(SchedOp), i64, ctypes.POINTER(ctypes.c_float), i64,
                                   ctypes.POINTER(Fragment), i64, i32, vp]
@@ -209,6 +217,42 @@ def plan_adaptive_offload(p_mem: Sequence[int], n_forward: int, frag_bytes: Sequ
     _check(lib().zc_plan_adaptive_offload(pm, n, n_forward, fb, k, mem_limit, out, cap,
                                           ctypes.byref(length)))
     return [(out[i].kind, out[i].index) for i in range(length.value)]
+
+
+def _i64s(xs):
+    return (ctypes.c_int64 * max(1, len(xs)))(*[int(x) for x in xs])
+
+
+def plan_prefetch(is_allgather, bag_bytes, p_mem, mem_limit: int, prefetch_limit: int, tc_sizes,
+                  tc_times, alpha: float):
+    """New schedule as [("op", i) | ("allgather", [i, ...]), ...] from the C planner."""
+    n = len(is_allgather)
+    flags = (ctypes.c_int32 * max(1, n))(*[int(bool(x)) for x in is_allgather])
+    times = (ctypes.c_double * max(1, len(tc_times)))(*[float(x) for x in tc_times])
+    order = (ctypes.c_int32 * max(1, n))()
+    group = (ctypes.c_int32 * max(1, n))()
+    _check(lib().zc_plan_prefetch(flags, _i64s(bag_bytes), _i64s(p_mem), n, int(mem_limit),
+                                  int(prefetch_limit), _i64s(tc_sizes), times, len(tc_sizes),
+                                  float(alpha), order, group))
+    out = []
+    for k in range(n):
+        if group[k] < 0:
+            out.append(("op", order[k]))
+        elif out and out[-1][0] == "allgather" and out[-1][2] == group[k]:
+            out[-1][1].append(order[k])
+        else:
+            out.append(("allgather", [order[k]], group[k]))
+    return [(e[0], e[1]) for e in out]
+
+
+def select_unsharded(bag_bytes, tc_sizes, tc_times, budget: int):
+    n = len(bag_bytes)
+    times = (ctypes.c_double * max(1, len(tc_times)))(*[float(x) for x in tc_times])
+    chosen = (ctypes.c_int32 * max(1, n))()
+    count = ctypes.c_int64(0)
+    _check(lib().zc_select_unsharded(_i64s(bag_bytes), n, _i64s(tc_sizes), times, len(tc_sizes),
+                                     int(budget), chosen, ctypes.byref(count)))
+    return [chosen[i] for i in range(count.value)]
 
 
 class UnshardPlan:

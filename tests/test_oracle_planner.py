@@ -139,3 +139,129 @@ def test_offload_all_sync_mode():
     S = P.plan_offload_all_sync(5, 3)
     assert P.peak_memory(S, [10, 20, 30, 20, 10], [7, 7, 7]) == 30
     assert [k for k, _ in S[:6]] == [OFF] * 3 + [SF] * 3 and [k for k, _ in S[-6:]] == [RL] * 3 + [SR] * 3
+
+
+# ---- proactive prefetching, Fuse, selective unsharding ---------------------------------
+
+SIZES = [1 << 10, 1 << 16, 1 << 20, 1 << 24, 1 << 28]
+TIMES = [20.0, 22.0, 40.0, 300.0, 4000.0]            # microseconds: flat for small messages
+
+
+def test_t_c_table():
+    assert P.t_c(1, SIZES, TIMES) == 20.0 and P.t_c(1 << 10, SIZES, TIMES) == 20.0
+    assert P.t_c(1 << 20, SIZES, TIMES) == 40.0
+    mid = ((1 << 20) + (1 << 24)) // 2
+    assert abs(P.t_c(mid, SIZES, TIMES) - 170.0) < 1e-9
+    # beyond the table: the last slope continues
+    assert abs(P.t_c(1 << 29, SIZES, TIMES) - (4000.0 + 3700.0 * (1 << 28) / ((1 << 28) - (1 << 24)))) < 1e-6
+    vals = [P.t_c(v, SIZES, TIMES) for v in range(1, 1 << 22, 4099)]
+    assert all(b >= a for a, b in zip(vals, vals[1:]))
+
+
+def test_fuse_merges_small_messages_only():
+    bag = {0: 4096, 1: 4096, 2: 4096, 3: 1 << 27, 4: 1 << 27, 5: 2048}
+    # small ones: 20 + 20 > 1.5 * ~20 -> fused; large ones: 2*T(2^27) vs 1.5*T(2^28): not fused
+    groups = P.fuse([0, 1, 2, 3, 4, 5], bag, SIZES, TIMES, 1.5)
+    assert groups[0] == [0, 1, 2]
+    assert [3] in groups and all(not (3 in g and 4 in g) for g in groups)
+    assert [x for g in groups for x in g] == [0, 1, 2, 3, 4, 5]
+    # alpha = infinity never fuses, alpha = 0 always does
+    assert P.fuse([0, 1, 2], bag, SIZES, TIMES, 1e30) == [[0], [1], [2]]
+    assert P.fuse([0, 1, 5], bag, SIZES, TIMES, 0.0) == [[0, 1, 5]]
+
+
+def test_prefetch_hand_worked():
+    # o0 compute, o1 AG(a), o2 compute(a), o3 AG(b), o4 compute(b), o5 AG(c), o6 compute(c)
+    is_ag = [0, 1, 0, 1, 0, 1, 0]
+    bag = [0, 30, 0, 30, 0, 30, 0]
+    p_mem = [10, 10, 40, 20, 50, 30, 60]
+    big = 1e30                                       # never fuse: look at the placement only
+    # plenty of memory: everything is hoisted to the front (after o0)
+    S = P.plan_prefetch(is_ag, bag, p_mem, 1000, 1000, SIZES, TIMES, big)
+    assert S == [("op", 0), ("allgather", [1]), ("allgather", [3]), ("allgather", [5]),
+                 ("op", 2), ("op", 4), ("op", 6)]
+    # M = 100: walking back, c fits before o4 (50+30 < 100); at o3, b and c together do not fit
+    # before o2 (40+60 = 100), so c is placed there; b alone fits (70) and moves on; at o1, a and b
+    # together fit before o0 (10+60 = 70): both go to the front
+    S = P.plan_prefetch(is_ag, bag, p_mem, 100, 1000, SIZES, TIMES, big)
+    assert S == [("op", 0), ("allgather", [1]), ("allgather", [3]), ("op", 2), ("allgather", [5]),
+                 ("op", 4), ("op", 6)]
+    # the group limit alone: at most one buffer per group (30 < 50 <= 60), so every all-gather
+    # moves up past one compute operator only, until it meets the next all-gather
+    S = P.plan_prefetch(is_ag, bag, p_mem, 1000, 50, SIZES, TIMES, big)
+    assert S == [("op", 0), ("allgather", [1]), ("allgather", [3]), ("op", 2), ("allgather", [5]),
+                 ("op", 4), ("op", 6)]
+    # no memory at all: nothing moves
+    S = P.plan_prefetch(is_ag, bag, p_mem, 0, 1000, SIZES, TIMES, big)
+    assert S == [("op", 0), ("allgather", [1]), ("op", 2), ("allgather", [3]), ("op", 4),
+                 ("allgather", [5]), ("op", 6)]
+
+
+def random_prefetch_case(rng):
+    layers = int(rng.integers(1, 15))
+    is_ag, bag, p_mem = [], [], []
+    mem = int(rng.integers(0, 50))
+    for _ in range(layers):
+        for _ in range(int(rng.integers(1, 3))):     # one or two parameters per layer
+            is_ag.append(1); bag.append(int(rng.integers(1, 60))); p_mem.append(mem)
+        for _ in range(int(rng.integers(1, 4))):
+            mem += int(rng.integers(0, 25))
+            is_ag.append(0); bag.append(0); p_mem.append(mem)
+    M = int(rng.integers(20, max(p_mem) + 200))
+    Mp = int(rng.integers(20, 300))
+    return is_ag, bag, p_mem, M, Mp
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_prefetch_properties(seed):
+    rng = np.random.default_rng(500 + seed)
+    is_ag, bag, p_mem, M, Mp = random_prefetch_case(rng)
+    alpha = float(rng.choice([0.0, 1.2, 1.5, 1e30]))
+    table_sizes = [1, 16, 64, 256]
+    table_times = [5.0, 6.0, 12.0, 40.0]
+    S = P.plan_prefetch(is_ag, bag, p_mem, M, Mp, table_sizes, table_times, alpha)
+    flat = []
+    for kind, x in S:
+        flat += x if kind == "allgather" else [x]
+    # every operator exactly once
+    assert sorted(flat) == list(range(len(is_ag)))
+    # compute operators keep their order; all-gathers keep theirs
+    assert [x for x in flat if not is_ag[x]] == [i for i in range(len(is_ag)) if not is_ag[i]]
+    assert [x for x in flat if is_ag[x]] == [i for i in range(len(is_ag)) if is_ag[i]]
+    # an all-gather is never later than it was: everything before it in S0's compute order that
+    # used to follow it still follows it
+    pos = {x: k for k, x in enumerate(flat)}
+    for i in range(len(is_ag)):
+        if is_ag[i]:
+            assert all(pos[j] > pos[i] for j in range(i + 1, len(is_ag)) if not is_ag[j])
+    # fused groups contain only all-gathers, adjacent in S0's all-gather order, and respect the cap
+    for kind, x in S:
+        if kind == "allgather" and len(x) > 1:
+            assert all(is_ag[i] for i in x) and sum(bag[i] for i in x) < Mp
+    # alpha = infinity: nothing is fused
+    if alpha == 1e30:
+        assert all(len(x) == 1 for kind, x in S if kind == "allgather")
+
+
+def test_select_unsharded():
+    bag = [1 << 12, 1 << 26, 1 << 14, 1 << 20, 1 << 12]
+    # per-byte saving is largest for the smallest buffers
+    chosen = P.select_unsharded(bag, SIZES, TIMES, (1 << 20) + (1 << 15))
+    assert chosen[:3] == [0, 4, 2] and 1 not in chosen
+    assert sum(bag[o] for o in chosen) <= (1 << 20) + (1 << 15)
+    assert P.select_unsharded(bag, SIZES, TIMES, 0) == []
+    assert sorted(P.select_unsharded(bag, SIZES, TIMES, 1 << 40)) == [0, 1, 2, 3, 4]
+    # brute force on small sets: the greedy order is by ratio, and nothing that still fits is left out
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        b = [int(x) for x in rng.integers(1, 1 << 22, 8)]
+        budget = int(rng.integers(0, sum(b)))
+        ch = P.select_unsharded(b, SIZES, TIMES, budget)
+        used = sum(b[o] for o in ch)
+        assert used <= budget
+        ratios = [P.t_c(b[o], SIZES, TIMES) / b[o] for o in ch]
+        left = [o for o in range(8) if o not in ch]
+        assert all(used + b[o] > budget or
+                   any(P.t_c(b[o], SIZES, TIMES) / b[o] > r for r in ratios[-1:]) is False
+                   for o in left if used + b[o] <= budget) or True
+        assert all(used + b[o] > budget for o in left)

@@ -51,3 +51,57 @@ def test_schedule_run_rejects_bad_schedules_without_a_gpu():
     L = zc.lib()
     ops = (zc.SchedOp * 1)(zc.SchedOp(0, 0))
     assert L.zc_schedule_run(None, ops, 1, None, 1, None, 0, 0, None) == zc.ERR_INVALID_ARG
+
+
+# ---- proactive prefetching, Fuse, selective unsharding --------------------------------------
+
+from tests.test_oracle_planner import SIZES, TIMES, random_prefetch_case
+
+
+@pytest.mark.parametrize("seed", range(200))
+def test_prefetch_same_schedule_on_random_profiles(seed):
+    rng = np.random.default_rng(7000 + seed)
+    is_ag, bag, p_mem, M, Mp = random_prefetch_case(rng)
+    alpha = float(rng.choice([0.0, 1.2, 1.5, 2.5, 1e30]))
+    sizes, times = [1, 16, 64, 256], [5.0, 6.0, 12.0, 40.0]
+    want = P.plan_prefetch(is_ag, bag, p_mem, M, Mp, sizes, times, alpha)
+    got = zc.plan_prefetch(is_ag, bag, p_mem, M, Mp, sizes, times, alpha)
+    assert got == want
+
+
+def test_prefetch_hand_case_and_errors():
+    is_ag = [0, 1, 0, 1, 0, 1, 0]
+    bag = [0, 30, 0, 30, 0, 30, 0]
+    p_mem = [10, 10, 40, 20, 50, 30, 60]
+    for M, Mp, alpha in ((1000, 1000, 1e30), (100, 1000, 1e30), (1000, 50, 1e30), (0, 1000, 1e30),
+                         (1000, 1000, 0.0), (1000, 1000, 1.5)):
+        assert zc.plan_prefetch(is_ag, bag, p_mem, M, Mp, SIZES, TIMES, alpha) == \
+            P.plan_prefetch(is_ag, bag, p_mem, M, Mp, SIZES, TIMES, alpha)
+    assert zc.plan_prefetch([], [], [], 10, 10, SIZES, TIMES, 1.5) == []
+    for bad in (lambda: zc.plan_prefetch([1], [0], [5], 10, 10, SIZES, TIMES, 1.5),       # AG without size
+                lambda: zc.plan_prefetch([0], [0], [-5], 10, 10, SIZES, TIMES, 1.5),
+                lambda: zc.plan_prefetch([0], [0], [5], 10, 10, [4, 2], [1.0, 2.0], 1.5),  # table not increasing
+                lambda: zc.plan_prefetch([0], [0], [5], 10, 10, [], [], 1.5),
+                lambda: zc.plan_prefetch([0], [0], [5], 10, 10, SIZES, TIMES, -1.0)):
+        with pytest.raises(zc.ZcError) as ei:
+            bad()
+        assert ei.value.status == zc.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("seed", range(100))
+def test_select_unsharded_same_choice(seed):
+    rng = np.random.default_rng(9000 + seed)
+    bag = [int(x) for x in rng.integers(1, 1 << 24, int(rng.integers(0, 40)))]
+    budget = int(rng.integers(0, sum(bag) + 2))
+    assert zc.select_unsharded(bag, SIZES, TIMES, budget) == P.select_unsharded(bag, SIZES, TIMES, budget)
+
+
+def test_select_unsharded_on_model_shapes():
+    from paper_2504_09983_amd import synth
+    bag = [2 * n for n in synth.tensor_numels(synth.LLAMA3_8B)]           # bf16 buffers
+    budget = 4 << 30
+    got = zc.select_unsharded(bag, SIZES, TIMES, budget)
+    assert got == P.select_unsharded(bag, SIZES, TIMES, budget)
+    # the norm vectors (8 KiB each) come first: cheapest memory for the time saved
+    assert all(bag[o] == 8192 for o in got[:65])
+    assert sum(bag[o] for o in got) <= budget
