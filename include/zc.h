@@ -356,6 +356,8 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
  *   "copy.waves_per_cu", "cast.waves_per_cu", "accum.waves_per_cu"  the same cap for
  *                      unshard, the cast and gradient accumulation
  *   "copy.nontemporal"  non-temporal accesses in cast and unshard
+ *   "launch.max_grid"  workgroups per launch (default 2^30); larger jobs are cut into
+ *                      several launches
  *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default)
  *   "offload.zc_waves_per_cu"  resident-wave cap of the zero-copy kernel (0 = none)
  *   "offload.max_ahead" 1 (default) = the staged ring blocks the host so that it never runs

@@ -14,7 +14,6 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAccBlock = 64;
 constexpr int kAccRows = 4;
-constexpr int64_t kAccMaxGrid = int64_t(1) << 30;
 
 // The sum is formed in fp64 (the product of two fp32 values is exact there) and
 // rounded to fp32 once.
@@ -121,6 +120,7 @@ extern "C" zc_status zc_grad_accumulate(float *acc, const void *micro, zc_dtype 
             ntiles = 1;
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds((int)tune().accum_waves_per_cu, kAccBlock, &lds));
+        const int64_t kAccMaxGrid = tune().launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kAccMaxGrid) {
             const int64_t count = (ntiles - tile0) < kAccMaxGrid ? (ntiles - tile0) : kAccMaxGrid;
             if (bf16)

@@ -329,7 +329,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds(waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu, block, &lds));
         VecLaunch a{dim3(1), lds, stream, p, m, v, g, bf16_out, n, 0, s, skip_flag};
-        const int64_t kMaxGrid = int64_t(1) << 30;
+        const int64_t kMaxGrid = t.launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             a.grid = dim3((unsigned)count);

@@ -46,7 +46,6 @@ __device__ __forceinline__ uint32_t cast_rne(float x)
 
 constexpr int kCopyBlock = 64;  // one wave per workgroup: finest dispatch granularity
 constexpr int kCastRows = 4;    // 4 x 256 elements per workgroup tile
-constexpr int64_t kMaxGrid = int64_t(1) << 30;
 
 // Requires src 16-byte and dst 8-byte aligned.  One tile per workgroup; `tile0`
 // is the tile of workgroup 0 (launches are cut to keep the grid below 2^31).
@@ -240,6 +239,7 @@ zc_status zc_cast_bf16(const float *src, uint16_t *dst, int64_t n, void *hip_str
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds((int)t.cast_waves_per_cu, kCopyBlock, &lds));
+        const int64_t kMaxGrid = t.launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             if (t.copy_nontemporal)
@@ -377,6 +377,7 @@ zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void
     const Tune &t = tune();
     size_t lds = 0;
     ZC_TRY(occupancy_cap_lds((int)t.copy_waves_per_cu, kCopyBlock, &lds));
+    const int64_t kMaxGrid = t.launch_max_grid;
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int64_t tile0 = 0; tile0 < plan->ntiles; tile0 += kMaxGrid) {
         const int64_t left = plan->ntiles - tile0;

@@ -37,6 +37,7 @@ struct Tune {
     int64_t cast_waves_per_cu = 24;
     int64_t accum_waves_per_cu = 24;
     int64_t copy_nontemporal = 1;
+    int64_t launch_max_grid = int64_t(1) << 30;
     int64_t offload_zero_copy = 1;
     int64_t offload_zc_waves_per_cu = 0;
     int64_t offload_max_ahead = 1;

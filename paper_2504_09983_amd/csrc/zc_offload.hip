@@ -19,10 +19,11 @@
 //   d2h stream : wait(updated)   -> 3 x hipMemcpyAsync slot->host -> record(slot free)
 //
 // Measured on MI355X the ring reaches the plain-memcpy ceiling of the link when
-// the caller synchronises between steps, but with several steps queued the
-// runtime now and then (about one process in five) routes the copy-backs through
-// a path that runs at ~10 GB/s, halving the step rate; the zero-copy kernel
-// holds ~95 % of that ceiling every time, which is why it is the default.
+// the caller synchronises between steps.  The runtime executes the copy-backs as
+// copy kernels of its own, and with several steps queued those now and then
+// (about one process in five) run at ~10 GB/s, halving the step rate; the
+// zero-copy kernel holds ~95 % of the ceiling every time, which is why it is the
+// default.
 #include <chrono>
 #include <new>
 #include <vector>

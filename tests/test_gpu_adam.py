@@ -227,3 +227,32 @@ def test_runs_on_a_side_stream():
     m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
     oracle.adam_step(p, m, v, synth.host_grads_f32(n, 1), step=1, **HP)
     assert_state_close(host_f32(dp), host_f32(dm), host_f32(dv), p, m, v, tag="stream")
+
+
+def test_jobs_cut_into_several_launches():
+    """A tiny launch limit forces the multi-launch path (tile offsets) of every tiled kernel."""
+    old = zc.tune_get("launch.max_grid")
+    zc.tune_set("launch.max_grid", 7)
+    try:
+        n = 256 * 2 * 4 * 23 + 1031          # 23+ tiles of the default shape -> 4 launches
+        gpu, cpu = run_both(n, 2, g_bf16=True, seed=3)
+        check(gpu, cpu, tag="cut launches", steps=2)
+        x = synth.host_params(n, 5)
+        src = dev_f32(x)
+        dst = torch.zeros(n, dtype=torch.int16, device=DEV)
+        zc.cast_bf16(src, dst, n)
+        acc = dev_f32(np.zeros(n, np.float32))
+        zc.grad_accumulate(acc, src, zc.F32, n, 0.5)
+        outs = [torch.zeros(k, dtype=torch.int16, device=DEV) for k in (n // 3, n - n // 3)]
+        plan = zc.unshard_plan_create([(0, outs[0], n // 3), (n // 3, outs[1], n - n // 3)], n)
+        zc.unshard(plan, dst)
+        sync()
+        plan.destroy()
+        want = oracle.cast_bf16(x)
+        assert np.array_equal(host_u16(dst), want)
+        assert np.array_equal(np.concatenate([host_u16(o) for o in outs]), want)
+        a = np.zeros(n, np.float32)
+        oracle.grad_accumulate(a, x, 0.5)
+        assert np.array_equal(host_f32(acc), a)
+    finally:
+        zc.tune_set("launch.max_grid", old)
