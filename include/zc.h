@@ -107,6 +107,40 @@ zc_status zc_adam_step(float *p, float *m, float *v, const void *g, zc_dtype g_d
                        const int32_t *skip_flag, void *hip_stream);
 
 /*
+ * The same step with per-range hyper-parameters and a device-side gradient scale
+ * (weight decay is usually switched off for norm vectors and biases; the clipping
+ * coefficient and the loss scale are known on the GPU before they are on the host).
+ *   ranges[r]      HOST, sorted by begin, non-overlapping, inside [0, n): elements
+ *                  [begin, end) use lr = hp->lr * lr_scale (one fp32 product) and
+ *                  the range's weight_decay; elements outside every range use *hp
+ *   grad_scale_dev DEVICE float or NULL: gradients are multiplied by
+ *                  fl32(hp->grad_scale * *grad_scale_dev), read at execution time
+ * Everything else as zc_adam_step.  Each stretch is one launch; the result is
+ * bit-identical to calling zc_adam_step on the stretches one by one.
+ */
+typedef struct {
+    int64_t begin;
+    int64_t end;
+    float lr_scale;
+    float weight_decay;
+} zc_param_range;
+zc_status zc_adam_step_groups(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,
+                              int64_t n, const zc_adam_hparams *hp, const zc_param_range *ranges,
+                              int64_t nranges, uint16_t *bf16_out, const int32_t *skip_flag,
+                              const float *grad_scale_dev, void *hip_stream);
+
+/*
+ * Gradient-clipping coefficient and loss-scale removal on the GPU, from the
+ * squared norm that zc_grad_sqnorm wrote (of the still loss-scaled gradients):
+ *   norm = sqrt(*sqnorm) * inv_loss_scale
+ *   *scale_out = fl32(inv_loss_scale * min(1, max_norm / (norm + 1e-6)))   (max_norm = 0: no clipping)
+ * sqnorm, scale_out DEVICE float.  The result is what zc_adam_step_groups takes
+ * as grad_scale_dev, so norm -> coefficient -> step needs no host round trip.
+ */
+zc_status zc_clip_scale(const float *sqnorm, float max_norm, float inv_loss_scale,
+                        float *scale_out, void *hip_stream);
+
+/*
  * Standalone fp32 -> bf16 copy into the all-gather send buffer (paper: bf16
  * compute copies of fp32 masters, Experimental settings; the shards are what
  * the all-gather sends, Fully-sharded approach).  Round-to-nearest-even; NaN

@@ -63,6 +63,8 @@ def _prepare(lib):
     lib.zco_unshard.restype = None
     lib.zco_grad_accumulate.argtypes = [vp, vp, i32, i64, f32]
     lib.zco_grad_accumulate.restype = None
+    lib.zco_clip_scale.argtypes = [f32, f32, f32]
+    lib.zco_clip_scale.restype = f32
     return lib
 
 
@@ -115,6 +117,34 @@ def adam_step(p, m, v, g, *, lr, beta1, beta2, eps, weight_decay, step,
                           float(np.float32(beta2)), float(np.float32(eps)),
                           float(np.float32(weight_decay)), float(np.float32(grad_scale)),
                           int(step), int(mode), out_ptr, 1 if skip else 0)
+
+
+def adam_step_groups(p, m, v, g, *, ranges=(), lr, weight_decay, grad_scale=1.0,
+                     grad_scale_dev=None, bf16_out=None, **hp):
+    """The step with per-range hyper-parameters, written as what it means: every stretch of
+    the partition gets a plain adam_step with its own lr and weight decay.
+    ranges = [(begin, end, lr_scale, weight_decay)], sorted, disjoint; the rest uses lr / weight_decay.
+    grad_scale_dev models a scale that lives on the device: the effective scale is the fp32
+    product grad_scale * grad_scale_dev."""
+    n = p.size
+    scale = np.float32(grad_scale)
+    if grad_scale_dev is not None:
+        scale = np.float32(scale * np.float32(grad_scale_dev))
+    pieces, at = [], 0
+    for b, e, lr_scale, wd in ranges:
+        pieces.append((at, b, np.float32(lr), weight_decay))
+        pieces.append((b, e, np.float32(np.float32(lr) * np.float32(lr_scale)), wd))
+        at = e
+    pieces.append((at, n, np.float32(lr), weight_decay))
+    for b, e, lr_here, wd_here in pieces:
+        if e > b:
+            adam_step(p[b:e], m[b:e], v[b:e], g[b:e], lr=lr_here, weight_decay=wd_here,
+                      grad_scale=scale, bf16_out=None if bf16_out is None else bf16_out[b:e], **hp)
+
+
+def clip_scale(sqnorm, max_norm: float, inv_loss_scale: float = 1.0) -> np.float32:
+    return np.float32(_load().zco_clip_scale(float(np.float32(sqnorm)), float(np.float32(max_norm)),
+                                             float(np.float32(inv_loss_scale))))
 
 
 def cast_bf16(src: np.ndarray) -> np.ndarray:

@@ -184,3 +184,21 @@ void zco_grad_accumulate(float *acc, const void *micro, int micro_is_bf16, int64
         acc[i] = (float)((double)acc[i] + gi * scale);
     }
 }
+
+/*
+ * Gradient-clipping coefficient with loss-scale removal (the usual mixed-precision
+ * recipe; not in the paper): norm = sqrt(sqnorm) * inv_loss_scale,
+ * scale = inv_loss_scale * min(1, max_norm / (norm + 1e-6)); max_norm = 0 means no
+ * clipping.  Double arithmetic, one rounding to fp32.
+ */
+float zco_clip_scale(float sqnorm, float max_norm, float inv_loss_scale)
+{
+    const double norm = sqrt((double)sqnorm) * (double)inv_loss_scale;
+    double coef = 1.0;
+    if (max_norm > 0.0f) {
+        coef = (double)max_norm / (norm + 1e-6);
+        if (coef > 1.0)
+            coef = 1.0;
+    }
+    return (float)((double)inv_loss_scale * coef);
+}

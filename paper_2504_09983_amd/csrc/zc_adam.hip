@@ -30,6 +30,13 @@ struct AdamScalars {
     int l2;
 };
 
+// Device-resident controls read at execution time: a skip flag (overflowed step) and
+// an extra gradient scale (clipping coefficient / loss-scale removal computed on the GPU).
+struct DevCtl {
+    const int32_t *skip;
+    const float *gscale;
+};
+
 static AdamScalars make_scalars(const zc_adam_hparams *hp)
 {
     AdamScalars s;
@@ -132,11 +139,12 @@ template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH, bool GUARD>
 __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restrict__ m4,
                                           f32x4 *__restrict__ v4, const void *__restrict__ g,
                                           u32x2 *__restrict__ out2, int64_t first, int64_t nvec,
-                                          const AdamScalars &s, const int32_t *__restrict__ skip)
+                                          const AdamScalars &s_in, DevCtl ctl)
 {
-    // The skip flag is fetched together with the data and only tested before the
-    // first store, so its latency hides behind the tile's own loads.
-    const int32_t skip_now = skip ? *skip : 0;
+    // The skip flag and the device-side scale are fetched together with the data and only
+    // used after the tile's loads have been issued, so their latency hides behind them.
+    const int32_t skip_now = ctl.skip ? *ctl.skip : 0;
+    const float dev_scale = ctl.gscale ? *ctl.gscale : 1.0f;
     f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -158,6 +166,11 @@ __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restr
     }
     if (skip_now != 0)
         return;
+    AdamScalars s = s_in;
+    if (ctl.gscale) {
+        s.gscalef = s_in.gscalef * dev_scale;  // one fp32 product, the same in every variant
+        s.gscale = (double)s.gscalef;
+    }
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int64_t i = first + (int64_t)r * BLOCK;
@@ -192,8 +205,7 @@ __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(float *__restrict__ p, 
                                                          float *__restrict__ v,
                                                          const void *__restrict__ g,
                                                          uint16_t *__restrict__ out, int64_t n,
-                                                         int64_t tile0, AdamScalars s,
-                                                         const int32_t *__restrict__ skip)
+                                                         int64_t tile0, AdamScalars s, DevCtl ctl)
 {
     const int64_t nvec = n >> 2;
     f32x4 *p4 = reinterpret_cast<f32x4 *>(p);
@@ -205,13 +217,17 @@ __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(float *__restrict__ p, 
     const int64_t tile = tile0 + blockIdx.x;
     const int64_t first = tile * kTileVecs + threadIdx.x;
     if ((tile + 1) * kTileVecs <= nvec)
-        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false>(p4, m4, v4, g, out2, first, nvec, s, skip);
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false>(p4, m4, v4, g, out2, first, nvec, s, ctl);
     else
-        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true>(p4, m4, v4, g, out2, first, nvec, s, skip);
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true>(p4, m4, v4, g, out2, first, nvec, s, ctl);
 
     // The last n % 4 elements, one lane each, in the very first workgroup.
     const int64_t i = (nvec << 2) + threadIdx.x;
-    if (tile == 0 && threadIdx.x < 4 && i < n && !(skip && *skip != 0)) {
+    if (tile == 0 && threadIdx.x < 4 && i < n && !(ctl.skip && *ctl.skip != 0)) {
+        if (ctl.gscale) {
+            s.gscalef = s.gscalef * *ctl.gscale;
+            s.gscale = (double)s.gscalef;
+        }
         float pe = p[i], me = m[i], ve = v[i];
         float ge;
         if constexpr (G_BF16)
@@ -233,11 +249,14 @@ __global__ __launch_bounds__(256) void adam_scalar_kernel(float *__restrict__ p,
                                                           float *__restrict__ v,
                                                           const void *__restrict__ g,
                                                           uint16_t *__restrict__ out, int64_t n,
-                                                          AdamScalars s,
-                                                          const int32_t *__restrict__ skip)
+                                                          AdamScalars s, DevCtl ctl)
 {
-    if (skip && *skip != 0)
+    if (ctl.skip && *ctl.skip != 0)
         return;
+    if (ctl.gscale) {
+        s.gscalef = s.gscalef * *ctl.gscale;
+        s.gscale = (double)s.gscalef;
+    }
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
         float pe = p[i], me = m[i], ve = v[i];
@@ -264,14 +283,14 @@ struct VecLaunch {
     uint16_t *out;
     int64_t n, tile0;
     AdamScalars s;
-    const int32_t *skip;
+    DevCtl ctl;
 };
 
 template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
 static void launch_vec(const VecLaunch &a)
 {
     hipLaunchKernelGGL((adam_vec_kernel<ROWS, BLOCK, G_BF16, NT, ARITH>), a.grid, dim3(BLOCK), a.lds,
-                       a.stream, a.p, a.m, a.v, a.g, a.out, a.n, a.tile0, a.s, a.skip);
+                       a.stream, a.p, a.m, a.v, a.g, a.out, a.n, a.tile0, a.s, a.ctl);
 }
 
 template <int ROWS, int BLOCK, bool G_BF16, bool NT>
@@ -307,8 +326,9 @@ static void pick_rows(int rows, bool g_bf16, bool nt, int arith, const VecLaunch
 
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
-                      hipStream_t stream, int waves_per_cu)
+                      hipStream_t stream, int waves_per_cu, const float *grad_scale_dev)
 {
+    const DevCtl ctl{skip_flag, grad_scale_dev};
     if (n == 0)
         return ZC_OK;
     const AdamScalars s = make_scalars(hp);
@@ -328,7 +348,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds(waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu, block, &lds));
-        VecLaunch a{dim3(1), lds, stream, p, m, v, g, bf16_out, n, 0, s, skip_flag};
+        VecLaunch a{dim3(1), lds, stream, p, m, v, g, bf16_out, n, 0, s, ctl};
         const int64_t kMaxGrid = t.launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
@@ -348,7 +368,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
         const dim3 grid((unsigned)blocks);
 #define ZC_SCALAR(GB, AR)                                                                             \
     hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, g, bf16_out, \
-                       n, s, skip_flag)
+                       n, s, ctl)
         if (g_bf16) {
             if (arith == 0) ZC_SCALAR(true, 0);
             else if (arith == 1) ZC_SCALAR(true, 1);
@@ -366,11 +386,11 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
 
 }  // namespace zc
 
-extern "C" zc_status zc_adam_step(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,
-                                  int64_t n, const zc_adam_hparams *hp, uint16_t *bf16_out,
-                                  const int32_t *skip_flag, void *hip_stream)
+namespace zc {
+
+static zc_status check_adam_args(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
+                                 const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag)
 {
-    using namespace zc;
     if (n < 0)
         return fail(ZC_ERR_INVALID_ARG, "n is negative (%lld)", (long long)n);
     if (n > kMaxElements)
@@ -393,5 +413,99 @@ extern "C" zc_status zc_adam_step(float *p, float *m, float *v, const void *g, z
         (const void *)v == g || (void *)bf16_out == (void *)p || (void *)bf16_out == (void *)m ||
         (void *)bf16_out == (void *)v || (const void *)bf16_out == g)
         return fail(ZC_ERR_INVALID_ARG, "p, m, v, g, bf16_out must be distinct buffers");
+    return ZC_OK;
+}
+
+// One-lane kernel: clipping coefficient and loss-scale removal from the squared norm.
+__global__ void clip_scale_kernel(const float *__restrict__ sqnorm, double max_norm, double inv_loss_scale,
+                                  float *__restrict__ scale_out)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0)
+        return;
+    const double norm = sqrt((double)*sqnorm) * inv_loss_scale;
+    double coef = 1.0;
+    if (max_norm > 0.0) {
+        coef = max_norm / (norm + 1e-6);
+        if (coef > 1.0)
+            coef = 1.0;
+    }
+    *scale_out = (float)(inv_loss_scale * coef);
+}
+
+}  // namespace zc
+
+extern "C" zc_status zc_adam_step(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,
+                                  int64_t n, const zc_adam_hparams *hp, uint16_t *bf16_out,
+                                  const int32_t *skip_flag, void *hip_stream)
+{
+    using namespace zc;
+    ZC_TRY(check_adam_args(p, m, v, g, g_dtype, n, hp, bf16_out, skip_flag));
+    if (n == 0)
+        return ZC_OK;
     return launch_adam(p, m, v, g, g_dtype, n, hp, bf16_out, skip_flag, (hipStream_t)hip_stream);
+}
+
+extern "C" zc_status zc_adam_step_groups(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,
+                                         int64_t n, const zc_adam_hparams *hp,
+                                         const zc_param_range *ranges, int64_t nranges, uint16_t *bf16_out,
+                                         const int32_t *skip_flag, const float *grad_scale_dev,
+                                         void *hip_stream)
+{
+    using namespace zc;
+    ZC_TRY(check_adam_args(p, m, v, g, g_dtype, n, hp, bf16_out, skip_flag));
+    if (nranges < 0 || (nranges > 0 && !ranges))
+        return fail(ZC_ERR_INVALID_ARG, "nranges is negative or ranges is NULL");
+    if (grad_scale_dev && !aligned_to(grad_scale_dev, 4))
+        return fail(ZC_ERR_ALIGNMENT, "grad_scale_dev must be 4-byte aligned");
+    int64_t prev_end = 0;
+    for (int64_t r = 0; r < nranges; ++r) {
+        const zc_param_range &k = ranges[r];
+        if (k.begin < prev_end || k.end < k.begin || k.end > n)
+            return fail(ZC_ERR_INVALID_ARG, "range %lld: [%lld, %lld) is out of order or outside [0, n)",
+                        (long long)r, (long long)k.begin, (long long)k.end);
+        if (!(k.lr_scale == k.lr_scale) || k.lr_scale - k.lr_scale != 0.0f ||
+            !(k.weight_decay == k.weight_decay) || k.weight_decay - k.weight_decay != 0.0f)
+            return fail(ZC_ERR_INVALID_ARG, "range %lld: lr_scale and weight_decay must be finite", (long long)r);
+        prev_end = k.end;
+    }
+    if (n == 0)
+        return ZC_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t g_size = g_dtype == ZC_BF16 ? 2 : 4;
+    // One launch per stretch with its own hyper-parameters; uncovered stretches use *hp.
+    auto launch = [&](int64_t begin, int64_t end, const zc_adam_hparams &h) -> zc_status {
+        if (end <= begin)
+            return ZC_OK;
+        return launch_adam(p + begin, m + begin, v + begin, static_cast<const char *>(g) + begin * g_size,
+                           g_dtype, end - begin, &h, bf16_out ? bf16_out + begin : nullptr, skip_flag, stream,
+                           -1, grad_scale_dev);
+    };
+    int64_t at = 0;
+    for (int64_t r = 0; r < nranges; ++r) {
+        ZC_TRY(launch(at, ranges[r].begin, *hp));
+        zc_adam_hparams h = *hp;
+        h.lr = hp->lr * ranges[r].lr_scale;  // one fp32 product
+        h.weight_decay = ranges[r].weight_decay;
+        ZC_TRY(launch(ranges[r].begin, ranges[r].end, h));
+        at = ranges[r].end;
+    }
+    return launch(at, n, *hp);
+}
+
+extern "C" zc_status zc_clip_scale(const float *sqnorm, float max_norm, float inv_loss_scale,
+                                   float *scale_out, void *hip_stream)
+{
+    using namespace zc;
+    if (!sqnorm || !scale_out)
+        return fail(ZC_ERR_INVALID_ARG, "sqnorm and scale_out must not be NULL");
+    if (!aligned_to(sqnorm, 4) || !aligned_to(scale_out, 4))
+        return fail(ZC_ERR_ALIGNMENT, "sqnorm and scale_out must be 4-byte aligned");
+    if (!(max_norm >= 0.0f) || max_norm - max_norm != 0.0f)
+        return fail(ZC_ERR_INVALID_ARG, "max_norm must be finite and >= 0 (0 = no clipping)");
+    if (!(inv_loss_scale > 0.0f) || inv_loss_scale - inv_loss_scale != 0.0f)
+        return fail(ZC_ERR_INVALID_ARG, "inv_loss_scale must be finite and > 0");
+    hipLaunchKernelGGL(clip_scale_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, sqnorm,
+                       (double)max_norm, (double)inv_loss_scale, scale_out);
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
 }

@@ -59,9 +59,10 @@ zc_status check_dtype(zc_dtype t);
 
 // Enqueue the fused update over n elements; arguments already validated.
 // waves_per_cu < 0 takes the "adam.waves_per_cu" knob, otherwise overrides it.
+// grad_scale_dev (DEVICE, may be NULL) multiplies hp->grad_scale at execution time.
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
-                      hipStream_t stream, int waves_per_cu = -1);
+                      hipStream_t stream, int waves_per_cu = -1, const float *grad_scale_dev = nullptr);
 
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

@@ -48,6 +48,11 @@ class Fragment(ctypes.Structure):
 OP_COMPUTE, OP_OFFLOAD, OP_SYNC_FREE, OP_RELOAD, OP_SYNC_RELOAD = range(5)
 
 
+class ParamRange(ctypes.Structure):
+    _fields_ = [("begin", ctypes.c_int64), ("end", ctypes.c_int64), ("lr_scale", ctypes.c_float),
+                ("weight_decay", ctypes.c_float)]
+
+
 class Segment(ctypes.Structure):
     _fields_ = [("src_offset", ctypes.c_int64), ("dst", ctypes.c_void_p),
                 ("numel", ctypes.c_int64)]
@@ -77,6 +82,11 @@ def lib():
     L.zc_adam_step.restype = ctypes.c_int
     L.zc_adam_step.argtypes = [vp, vp, vp, vp, ctypes.c_int, i64, ctypes.POINTER(AdamHparams),
                                vp, vp, vp]
+    L.zc_adam_step_groups.restype = ctypes.c_int
+    L.zc_adam_step_groups.argtypes = [vp, vp, vp, vp, ctypes.c_int, i64, ctypes.POINTER(AdamHparams),
+                                      ctypes.POINTER(ParamRange), i64, vp, vp, vp, vp]
+    L.zc_clip_scale.restype = ctypes.c_int
+    L.zc_clip_scale.argtypes = [vp, ctypes.c_float, ctypes.c_float, vp, vp]
     L.zc_cast_bf16.restype = ctypes.c_int
     L.zc_cast_bf16.argtypes = [vp, vp, i64, vp]
     L.zc_flat_layout.restype = ctypes.c_int
@@ -174,6 +184,21 @@ def adam_step(p, m, v, g, g_dtype: int, n: int, hp: AdamHparams, bf16_out=None, 
     _check(lib().zc_adam_step(_addr(p), _addr(m), _addr(v), _addr(g), g_dtype, n,
                               ctypes.byref(hp), _addr(bf16_out), _addr(skip_flag),
                               _stream(stream)))
+
+
+def adam_step_groups(p, m, v, g, g_dtype: int, n: int, hp: AdamHparams, ranges=(), bf16_out=None,
+                     skip_flag=None, grad_scale_dev=None, stream=None) -> None:
+    """ranges = [(begin, end, lr_scale, weight_decay), ...]"""
+    arr = (ParamRange * max(1, len(ranges)))(*[ParamRange(int(b), int(e), float(s), float(w))
+                                               for b, e, s, w in ranges])
+    _check(lib().zc_adam_step_groups(_addr(p), _addr(m), _addr(v), _addr(g), g_dtype, n,
+                                     ctypes.byref(hp), arr, len(ranges), _addr(bf16_out),
+                                     _addr(skip_flag), _addr(grad_scale_dev), _stream(stream)))
+
+
+def clip_scale(sqnorm, max_norm: float, inv_loss_scale: float, scale_out, stream=None) -> None:
+    _check(lib().zc_clip_scale(_addr(sqnorm), max_norm, inv_loss_scale, _addr(scale_out),
+                               _stream(stream)))
 
 
 def cast_bf16(src, dst, n: int, stream=None) -> None:

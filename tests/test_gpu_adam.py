@@ -256,3 +256,55 @@ def test_jobs_cut_into_several_launches():
         assert np.array_equal(host_f32(acc), a)
     finally:
         zc.tune_set("launch.max_grid", old)
+
+
+def test_groups_and_device_side_clipping():
+    """norm -> clipping coefficient -> per-range step, all on the GPU, against the oracle."""
+    n = 200_000 + 37
+    ranges = [(0, 4096, 1.0, 0.0), (4096, 4096 + 8193, 0.5, 0.0), (100_000, 100_003, 2.0, 0.3),
+              (150_001, n, 1.0, 0.0)]                      # aligned, odd and tiny stretches
+    p = synth.host_params(n, 50)
+    m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
+    out = np.zeros(n, np.uint16)
+    dp, dm, dv = dev_f32(p), dev_f32(m), dev_f32(v)
+    dout = torch.zeros(n, dtype=torch.int16, device=DEV)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    scale = torch.zeros(1, dtype=torch.float32, device=DEV)
+    loss_scale = 1024.0
+    hpd = dict(HP)
+    for t in range(1, 4):
+        g = oracle.cast_bf16(synth.host_grads_f32(n, t) * np.float32(loss_scale))
+        dg = dev_u16(g)
+        zc.grad_sqnorm(dg, zc.BF16, n, norm, flag)
+        zc.clip_scale(norm, 0.05, 1.0 / loss_scale, scale)
+        zc.adam_step_groups(dp, dm, dv, dg, zc.BF16, n, zc.hparams(step=t, **hpd), ranges=ranges,
+                            bf16_out=dout, skip_flag=flag, grad_scale_dev=scale)
+        sync()
+        # the oracle takes the norm the GPU reduced (fp32) so that both clip from the same number
+        sq = np.float32(norm.item())
+        want_sq, bad = oracle.grad_sqnorm(g)
+        assert bad == 0 and abs(float(sq) - want_sq) <= 1e-6 * want_sq
+        c = oracle.clip_scale(sq, 0.05, 1.0 / loss_scale)
+        assert np.float32(scale.item()) == c and float(c) < 1.0 / loss_scale      # it did clip
+        oracle.adam_step_groups(p, m, v, g, ranges=ranges, step=t, grad_scale_dev=c, bf16_out=out, **hpd)
+    check((host_f32(dp), host_f32(dm), host_f32(dv), host_u16(dout)), (p, m, v, out), tag="groups",
+          steps=3, m_floor=1e-5)
+    # bit-identical to stretch-by-stretch calls of the plain entry point
+    a = [dev_f32(synth.host_params(n, 51)), dev_f32(np.zeros(n)), dev_f32(np.zeros(n))]
+    b = [x.clone() for x in a]
+    dg = dev_f32(synth.host_grads_f32(n, 9))
+    hp = zc.hparams(step=2, **hpd)
+    zc.adam_step_groups(*a, dg, zc.F32, n, hp, ranges=ranges)
+    cuts, at = [], 0
+    for b0, e0, ls, wd in ranges:
+        cuts += [(at, b0, hpd["lr"], hpd["weight_decay"]), (b0, e0, float(np.float32(hpd["lr"]) * np.float32(ls)), wd)]
+        at = e0
+    cuts.append((at, n, hpd["lr"], hpd["weight_decay"]))
+    for b0, e0, lr, wd in cuts:
+        if e0 > b0:
+            h = zc.hparams(step=2, **dict(hpd, lr=lr, weight_decay=wd))
+            zc.adam_step(*[x[b0:e0] for x in b], dg[b0:e0], zc.F32, e0 - b0, h)
+    sync()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)

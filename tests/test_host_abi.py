@@ -28,7 +28,9 @@ def test_library_loads_and_exports_every_declared_symbol():
             "zc_unshard_plan_create", "zc_unshard_plan_destroy", "zc_offload_create",
             "zc_offload_destroy", "zc_grad_sqnorm", "zc_flat_layout", "zc_last_error",
             "zc_version", "zc_tune_set", "zc_tune_get", "zc_per_tensor_layout", "zc_host_alloc",
-            "zc_host_free", "zc_offload_probe_link", "zc_grad_accumulate"} <= set(names)
+            "zc_host_free", "zc_offload_probe_link", "zc_grad_accumulate", "zc_adam_step_groups",
+            "zc_clip_scale", "zc_plan_adaptive_offload", "zc_plan_prefetch", "zc_select_unsharded",
+            "zc_schedule_run"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert zc.version() >= 100
@@ -71,6 +73,16 @@ def test_adam_step_rejects_bad_arguments_without_a_gpu():
     assert "mode" in zc.last_error() or "weight_decay" in zc.last_error()
     # n == 0 is a no-op even with NULL pointers
     zc.adam_step(0, 0, 0, 0, zc.F32, 0, hp, stream=0)
+    # per-range step: ranges must be sorted, disjoint and inside [0, n)
+    ok = (A, A + 64, A + 128, A + 192, zc.F32, 8, hp)
+    for bad in ([(4, 2, 1.0, 0.0)], [(0, 9, 1.0, 0.0)], [(0, 4, 1.0, 0.0), (3, 6, 1.0, 0.0)],
+                [(0, 4, float("nan"), 0.0)], [(-1, 4, 1.0, 0.0)]):
+        assert _status(zc.adam_step_groups, *ok, ranges=bad, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step_groups, *ok, grad_scale_dev=A + 1, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.clip_scale, 0, 1.0, 1.0, A, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.clip_scale, A, -1.0, 1.0, A + 4, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.clip_scale, A, 1.0, 0.0, A + 4, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.clip_scale, A + 2, 1.0, 1.0, A + 4, stream=0) == zc.ERR_ALIGNMENT
 
 
 def test_cast_and_sqnorm_reject_bad_arguments_without_a_gpu():

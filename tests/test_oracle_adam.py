@@ -442,3 +442,57 @@ def test_grad_accumulate_closed_forms():
     acc = np.zeros(3, np.float32)
     oracle.grad_accumulate(acc, f32([1.0, np.inf, np.nan]), 2.0)
     assert acc[0] == 2.0 and np.isinf(acc[1]) and np.isnan(acc[2])
+
+
+# ---- per-range hyper-parameters, clipping coefficient --------------------------------
+
+def test_groups_no_decay_range_and_lr_scale():
+    n = 1000
+    p, m, v = fresh(n, 20)
+    p0 = p.copy()
+    g = np.zeros(n, np.float32)
+    hp = dict(beta1=0.9, beta2=0.999, eps=1e-8, step=1)
+    # zero gradient: elements in the no-decay range do not move, the others decay
+    oracle.adam_step_groups(p, m, v, g, ranges=[(100, 300, 1.0, 0.0)], lr=1e-2, weight_decay=0.1, **hp)
+    lr, wd = float(np.float32(1e-2)), float(np.float32(0.1))
+    assert np.array_equal(p[100:300], p0[100:300])
+    want = (p0.astype(np.float64) * (1 - lr * wd)).astype(np.float32)
+    assert np.array_equal(p[:100], want[:100]) and np.array_equal(p[300:], want[300:])
+    # lr_scale scales the step: constant gradient, first step moves by lr*scale*sign(g)
+    p, m, v = fresh(n, 21)
+    p0 = p.copy()
+    g = np.full(n, 1e-3, np.float32)
+    oracle.adam_step_groups(p, m, v, g, ranges=[(0, 10, 0.5, 0.0), (500, 1000, 2.0, 0.0)],
+                            lr=1e-3, weight_decay=0.0, **hp)
+    d = p0.astype(np.float64) - p.astype(np.float64)
+    assert np.allclose(d[:10], 0.5e-3, rtol=1e-3) and np.allclose(d[10:500], 1e-3, rtol=1e-3)
+    assert np.allclose(d[500:], 2e-3, rtol=1e-3)
+    # no ranges == the plain step, bit for bit
+    a = fresh(n, 22)
+    b = [x.copy() for x in a]
+    g = synth.host_grads_f32(n, 2)
+    oracle.adam_step_groups(*a, g, lr=1e-4, weight_decay=0.01, **hp)
+    oracle.adam_step(*b, g, lr=1e-4, weight_decay=0.01, **hp)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    # device-side scale is a pre-multiplication by the fp32 product
+    a = fresh(n, 23); b = [x.copy() for x in a]
+    oracle.adam_step_groups(*a, g, lr=1e-4, weight_decay=0.01, grad_scale=0.5, grad_scale_dev=0.25, **hp)
+    oracle.adam_step(*b, g, lr=1e-4, weight_decay=0.01, grad_scale=0.125, **hp)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_clip_scale_closed_forms():
+    # norm 5 (sqnorm 25): no clipping needed for max_norm 10; clipped to 1/5 for max_norm 1
+    assert oracle.clip_scale(25.0, 10.0) == np.float32(1.0)
+    assert abs(float(oracle.clip_scale(25.0, 1.0)) - 1.0 / (5.0 + 1e-6)) < 1e-8
+    assert oracle.clip_scale(25.0, 0.0) == np.float32(1.0)            # 0 = off
+    # loss scale 1024: the scaled norm is 5*1024, the true norm 5
+    s = float(oracle.clip_scale(25.0 * 1024 * 1024, 1.0, 1.0 / 1024))
+    assert abs(s - (1.0 / 1024) / (5.0 + 1e-6)) < 1e-11
+    assert oracle.clip_scale(25.0 * 1024 * 1024, 10.0, 1.0 / 1024) == np.float32(1.0 / 1024)
+    # after scaling, the gradient norm is min(norm, max_norm)
+    g = synth.host_normal(10000, 1.0, 3)
+    sq, _ = oracle.grad_sqnorm(g)
+    c = float(oracle.clip_scale(sq, 7.0))
+    assert abs(np.sqrt(sq) * c - 7.0) < 1e-4
+    assert np.isnan(oracle.clip_scale(np.nan, 1.0)) and oracle.clip_scale(np.inf, 1.0) == 0.0

@@ -42,6 +42,10 @@ MUTATIONS = {
     "bf16_grads_wrong_index": ("        double gi = g_is_bf16 ? (double)zco_bf16_to_f32(g16[i])",
                                "        double gi = g_is_bf16 ? (double)zco_bf16_to_f32(g16[i / 2])"),
     "sqnorm_not_squared": ("acc += gi * gi;", "acc += gi;"),
+    "clip_without_sqrt": ("const double norm = sqrt((double)sqnorm) * (double)inv_loss_scale;",
+                          "const double norm = (double)sqnorm * (double)inv_loss_scale;"),
+    "clip_never_clamps": ("        if (coef > 1.0)\n            coef = 1.0;", "        if (0)\n            coef = 1.0;"),
+    "clip_forgets_loss_scale": ("return (float)((double)inv_loss_scale * coef);", "return (float)coef;"),
     "accumulate_overwrites": ("acc[i] = (float)((double)acc[i] + gi * scale);",
                               "acc[i] = (float)(gi * scale);"),
     "accumulate_ignores_scale": ("acc[i] = (float)((double)acc[i] + gi * scale);",
@@ -57,7 +61,8 @@ PINS = [
     A.test_against_torch_adam_l2_fp64, A.test_elementwise_independence_and_split_calls,
     A.test_bf16_grads_equal_upcast_fp32_grads, A.test_grad_scale_is_premultiplication,
     A.test_skip_touches_nothing_and_bf16_out_is_cast_of_p, A.test_nan_gradient_poisons_only_its_element,
-    A.test_padding_stays_zero, A.test_grad_accumulate_closed_forms, A.test_offload_definition_is_concatenation, A.test_grad_sqnorm,
+    A.test_padding_stays_zero, A.test_grad_accumulate_closed_forms, A.test_clip_scale_closed_forms,
+    A.test_groups_no_decay_range_and_lr_scale, A.test_offload_definition_is_concatenation, A.test_grad_sqnorm,
     C.test_all_bf16_values_round_trip, C.test_every_tie_goes_to_even, C.test_special_values,
     C.test_nearest_value_property_on_random_bits, C.test_library_conversion_agrees,
     C.test_unshard_brute_force_ragged, C.test_unshard_hash_property_and_ranks_spanned,
