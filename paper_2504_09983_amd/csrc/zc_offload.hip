@@ -44,8 +44,6 @@ struct zc_offload_ctx {
 
 namespace zc {
 
-hipStream_t offload_h2d_stream(zc_offload_ctx *ctx);
-
 static void destroy_ctx(zc_offload_ctx *c)
 {
     if (!c)
@@ -71,6 +69,7 @@ static void destroy_ctx(zc_offload_ctx *c)
     delete c;
 }
 
+// Accessors for the schedule executor, which lives in another translation unit.
 hipStream_t offload_h2d_stream(zc_offload_ctx *ctx) { return ctx->h2d; }
 hipStream_t offload_d2h_stream(zc_offload_ctx *ctx) { return ctx->d2h; }
 int offload_device(zc_offload_ctx *ctx) { return ctx->device; }

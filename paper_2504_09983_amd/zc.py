@@ -365,7 +365,8 @@ class OffloadCtx:
 
 
 class PinnedBuffer:
-    """Owns pinned host memory from zc_host_alloc; `.numpy(dtype)` views it without a copy."""
+    """Owns pinned host memory from zc_host_alloc; `.numpy(dtype)` views it without a copy.
+    The views do not keep the memory alive: drop them before `free()`."""
 
     def __init__(self, nbytes: int):
         ptr = ctypes.c_void_p(None)
