@@ -308,3 +308,59 @@ def test_groups_and_device_side_clipping():
     sync()
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+def test_whole_step_replays_from_a_hip_graph():
+    """grad-norm -> step (skip flag, fused bf16 copy) -> unshard captured once and replayed:
+    every replay must equal the same calls made eagerly (no allocation, no host sync, no memset
+    inside the calls once the library is warm)."""
+    n = 300_000 + 5
+    numels = [100_000, 7, 150_000, 50_000 - 2]
+    offs, shard, total = zc.flat_layout(numels, 1, 1)
+    assert total == n
+    hp = zc.hparams(step=3, **HP)
+
+    def fresh_state(seed):
+        return [dev_f32(synth.host_params(n, seed)), dev_f32(np.abs(synth.host_normal(n, 1e-4, seed + 1))),
+                dev_f32(np.abs(synth.host_normal(n, 1e-7, seed + 2)))]
+
+    state = fresh_state(60)
+    dg = dev_u16(oracle.cast_bf16(synth.host_grads_f32(n, 4)))
+    send = torch.zeros(n, dtype=torch.int16, device=DEV)
+    outs = [torch.zeros(k, dtype=torch.int16, device=DEV) for k in numels]
+    plan = zc.unshard_plan_create([(o, t, k) for o, t, k in zip(offs, outs, numels)], n)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+
+    def step(st, snd):
+        zc.grad_sqnorm(dg, zc.BF16, n, norm, flag)
+        zc.adam_step(*st, dg, zc.BF16, n, hp, bf16_out=snd, skip_flag=flag)
+        zc.unshard(plan, snd)
+
+    warm = [x.clone() for x in state]
+    step(warm, torch.zeros_like(send))            # warms the library's lazily created workspace
+    sync()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(state, send)
+    sync()
+    for replay in range(4):
+        ref = [x.clone() for x in state]
+        ref_send = torch.zeros_like(send)
+        graph.replay()
+        sync()
+        got_outs = [o.clone() for o in outs]
+        step(ref, ref_send)                        # eager, same inputs (state before the replay)
+        sync()
+        for x, y in zip(state, ref):
+            assert torch.equal(x, y), f"replay {replay}"
+        assert torch.equal(send, ref_send)
+        for a, b in zip(got_outs, outs):           # eager unshard of ref_send rewrote `outs`
+            assert torch.equal(a, b)
+        assert torch.equal(torch.cat(outs), ref_send)
+        # interleave unrelated eager work and a sync between replays
+        _ = (state[0] * 2).sum().item()
+    plan.destroy()
