@@ -85,6 +85,41 @@ def test_llama70b_shard_step_and_cast():
     torch.cuda.empty_cache()
 
 
+def test_llama70b_shard_every_element_after_step_one():
+    """Step 1 from m = v = 0 has a closed form in every element: m = (1-b1) g, v = (1-b2) g^2,
+    p = p0 (1 - lr wd) - lr g / (|g| + eps) up to rounding.  Checked over all 8.8 B elements with
+    torch as a double-precision calculator, in chunks (a property that holds at any size; the
+    windows above carry the element-by-element comparison with the oracle)."""
+    _, n, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_70B), 8, 1)
+    p, m, v, g = alloc_state(n, torch.bfloat16)
+    synth.device_normal_(g, synth.G_STD, seed=2001)
+    p0_head = p[:1 << 20].clone()
+    chunk = 1 << 27
+    # one launch over the whole shard; p0 is rebuilt from the seeded generator afterwards
+    zc.adam_step(p, m, v, g, zc.BF16, n, zc.hparams(step=1, **HP))
+    sync()
+    b1, b2 = float(np.float32(HP["beta1"])), float(np.float32(HP["beta2"]))
+    lr, eps, wd = (float(np.float32(HP[k])) for k in ("lr", "eps", "weight_decay"))
+    p0 = torch.empty(n, dtype=torch.float32, device=DEV)
+    synth.device_normal_(p0, synth.P_STD, seed=2)          # the same seeded stream as alloc_state
+    assert torch.equal(p0[:1 << 20], p0_head)
+    worst = 0.0
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        gd = g[s:e].double()
+        assert torch.equal(m[s:e], (gd * (1.0 - b1)).float()), f"m chunk@{s}"
+        assert torch.equal(v[s:e], ((gd * (1.0 - b2)) * gd).float()), f"v chunk@{s}"
+        want = p0[s:e].double() * (1.0 - lr * wd) - lr * gd / (gd.abs() + eps)
+        # one fp32 rounding of p plus ~1.2e-7 relative on the lr-sized term (m, v stored in fp32)
+        err = (p[s:e].double() - want).abs()
+        bound = 0.5 * torch.maximum(p[s:e].abs(), p0[s:e].abs()).double() * 2.0 ** -23 + 3e-7 * lr + 1e-12
+        worst = max(worst, float((err / bound).max()))
+        del gd, want, err, bound
+    assert worst <= 1.0, worst
+    del p, m, v, g, p0
+    torch.cuda.empty_cache()
+
+
 def test_mixtral_unshard_full_size():
     """BASELINE config 5: gathered flat bf16 buffer of 8 rank shards (rank-padded) unsharded
     into 995 separately allocated tensors; bit-exact layout check by index hash."""
