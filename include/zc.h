@@ -94,12 +94,15 @@ const char *zc_last_error(void);
  * p, m, v      DEVICE fp32[n], 4-byte aligned, updated in place.
  * g            DEVICE, fp32[n] (ZC_F32, 4-byte aligned) or bf16[n] bit
  *              patterns (ZC_BF16, 2-byte aligned); read only.
- * bf16_out     DEVICE uint16[n] or NULL; must not alias p, m, v, g.
+ * bf16_out     DEVICE uint16[n] or NULL.  No two of p, m, v, g, bf16_out may
+ *              share a byte (checked; ZC_ERR_INVALID_ARG).
  * skip_flag    DEVICE int32 or NULL; when *skip_flag != 0 at execution time
  *              the step leaves every buffer untouched (overflowed step).
  * n            elements, >= 0 (0 is a no-op); any size up to 2^40.
  * Vector (128-bit) access is used when p, m, v are 16-byte aligned and g,
- * bf16_out are aligned to 4 elements; otherwise a scalar kernel runs.
+ * bf16_out are aligned to 4 elements, also when all of them reach that alignment
+ * after the same 1-3 leading elements (a range cut out of a larger partition);
+ * otherwise a slower one-element-per-lane kernel runs.
  * Returns ZC_ERR_INVALID_ARG / ZC_ERR_ALIGNMENT before launching anything.
  */
 zc_status zc_adam_step(float *p, float *m, float *v, const void *g, zc_dtype g_dtype,

@@ -324,6 +324,30 @@ static void pick_rows(int rows, bool g_bf16, bool nt, int arith, const VecLaunch
     else pick_flags<4, BLOCK>(g_bf16, nt, arith, a);
 }
 
+static void launch_scalar(float *p, float *m, float *v, const void *g, bool g_bf16, int64_t n,
+                          uint16_t *bf16_out, const AdamScalars &s, DevCtl ctl, int arith, int cus,
+                          hipStream_t stream)
+{
+    int64_t blocks = (n + 255) / 256;
+    const int64_t cap = (int64_t)cus * 32;
+    if (blocks > cap)
+        blocks = cap;
+    const dim3 grid((unsigned)blocks);
+#define ZC_SCALAR(GB, AR)                                                                             \
+    hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, g, bf16_out, \
+                       n, s, ctl)
+    if (g_bf16) {
+        if (arith == 0) ZC_SCALAR(true, 0);
+        else if (arith == 1) ZC_SCALAR(true, 1);
+        else ZC_SCALAR(true, 2);
+    } else {
+        if (arith == 0) ZC_SCALAR(false, 0);
+        else if (arith == 1) ZC_SCALAR(false, 1);
+        else ZC_SCALAR(false, 2);
+    }
+#undef ZC_SCALAR
+}
+
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
                       hipStream_t stream, int waves_per_cu, const float *grad_scale_dev)
@@ -334,12 +358,48 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
     const AdamScalars s = make_scalars(hp);
     const Tune &t = tune();
     const bool g_bf16 = g_dtype == ZC_BF16;
-    const uintptr_t g_align = g_bf16 ? 8 : 16;
-    const bool vec_ok = aligned_to(p, 16) && aligned_to(m, 16) && aligned_to(v, 16) &&
-                        aligned_to(g, g_align) && (!bf16_out || aligned_to(bf16_out, 8));
+    const int64_t g_size = g_bf16 ? 2 : 4;
     const int arith = (int)t.adam_arith;
 
-    if (vec_ok) {
+    // A stretch that does not start on a 128-byte line of p (a parameter range cut out of a
+    // larger partition) still takes the vector kernel: the elements in front of the next
+    // line (at most 31) go to the one-element-per-lane kernel, after which every wave's
+    // 1 KiB row covers whole lines again (measured: 6.4 instead of 5.4 TB/s).  This needs the
+    // other arrays to reach vector alignment after the same number of elements; if only a
+    // 16-byte boundary can be reached together, that one is taken.  Elements are
+    // independent, so the order of the two launches does not matter.
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(p);
+    const int64_t to_line = (int64_t)((128 - pa % 128) % 128) / 4;
+    const int64_t to_vec = (int64_t)((16 - pa % 16) % 16) / 4;
+    auto vec_ok_after = [&](int64_t k) {
+        const char *gk = static_cast<const char *>(g) + k * g_size;
+        return k < n && aligned_to(p + k, 16) && aligned_to(m + k, 16) && aligned_to(v + k, 16) &&
+               aligned_to(gk, g_bf16 ? 8 : 16) && (!bf16_out || aligned_to(bf16_out + k, 8));
+    };
+    int64_t peel = -1;                     // -1: the whole stretch takes the scalar kernel
+    if (n >= 4096 && vec_ok_after(to_line))
+        peel = to_line;
+    else if (vec_ok_after(0))
+        peel = 0;
+    else if (vec_ok_after(to_vec))
+        peel = to_vec;
+
+    int cus = 0;
+    if (peel != 0)
+        ZC_TRY(num_cus(&cus));
+    if (peel < 0) {
+        launch_scalar(p, m, v, g, g_bf16, n, bf16_out, s, ctl, arith, cus, stream);
+    } else {
+        if (peel > 0) {
+            launch_scalar(p, m, v, g, g_bf16, peel, bf16_out, s, ctl, arith, cus, stream);
+            p += peel;
+            m += peel;
+            v += peel;
+            g = static_cast<const char *>(g) + peel * g_size;
+            if (bf16_out)
+                bf16_out += peel;
+            n -= peel;
+        }
         const int rows = (int)t.adam_rows, block = (int)t.adam_block;
         const int64_t tile_vecs = (int64_t)block * rows;
         const int64_t nvec = n >> 2;
@@ -358,27 +418,6 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             else if (block == 128) pick_rows<128>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
             else pick_rows<256>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
         }
-    } else {
-        int cus = 0;
-        ZC_TRY(num_cus(&cus));
-        int64_t blocks = (n + 255) / 256;
-        const int64_t cap = (int64_t)cus * 32;
-        if (blocks > cap)
-            blocks = cap;
-        const dim3 grid((unsigned)blocks);
-#define ZC_SCALAR(GB, AR)                                                                             \
-    hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, g, bf16_out, \
-                       n, s, ctl)
-        if (g_bf16) {
-            if (arith == 0) ZC_SCALAR(true, 0);
-            else if (arith == 1) ZC_SCALAR(true, 1);
-            else ZC_SCALAR(true, 2);
-        } else {
-            if (arith == 0) ZC_SCALAR(false, 0);
-            else if (arith == 1) ZC_SCALAR(false, 1);
-            else ZC_SCALAR(false, 2);
-        }
-#undef ZC_SCALAR
     }
     ZC_HIP(hipGetLastError());
     return ZC_OK;
@@ -409,10 +448,16 @@ static zc_status check_adam_args(float *p, float *m, float *v, const void *g, zc
         return fail(ZC_ERR_ALIGNMENT, "bf16_out must be 2-byte aligned");
     if (skip_flag && !aligned_to(skip_flag, 4))
         return fail(ZC_ERR_ALIGNMENT, "skip_flag must be 4-byte aligned");
-    if (p == m || p == v || m == v || (const void *)p == g || (const void *)m == g ||
-        (const void *)v == g || (void *)bf16_out == (void *)p || (void *)bf16_out == (void *)m ||
-        (void *)bf16_out == (void *)v || (const void *)bf16_out == g)
-        return fail(ZC_ERR_INVALID_ARG, "p, m, v, g, bf16_out must be distinct buffers");
+    // The kernel reads every array through __restrict__ pointers: no two may share a byte.
+    struct Span { uintptr_t lo, hi; };
+    const uintptr_t n4 = (uintptr_t)n * 4, ng = (uintptr_t)n * (g_dtype == ZC_BF16 ? 2 : 4);
+    const Span spans[5] = {{(uintptr_t)p, (uintptr_t)p + n4}, {(uintptr_t)m, (uintptr_t)m + n4},
+                           {(uintptr_t)v, (uintptr_t)v + n4}, {(uintptr_t)g, (uintptr_t)g + ng},
+                           {(uintptr_t)bf16_out, (uintptr_t)bf16_out + (bf16_out ? (uintptr_t)n * 2 : 0)}};
+    for (int a = 0; a < 5; ++a)
+        for (int b = a + 1; b < 5; ++b)
+            if (spans[a].lo < spans[b].hi && spans[b].lo < spans[a].hi)
+                return fail(ZC_ERR_INVALID_ARG, "p, m, v, g, bf16_out must not overlap");
     return ZC_OK;
 }
 

@@ -105,6 +105,50 @@ def test_misaligned_pointers(offset, g_bf16):
     check(gpu, cpu, tag=f"offset={offset}", steps=2)
 
 
+@pytest.mark.parametrize("shifts", [(0, 1, 2, 3, 1), (1, 1, 1, 2, 1), (3, 3, 3, 3, 0), (0, 0, 0, 0, 1)])
+def test_arrays_misaligned_differently(shifts):
+    """Arrays that do not reach a 16-byte boundary after the same number of elements take
+    the one-element-per-lane kernel from start to end; same bits as the aligned call."""
+    n = 70001
+    p = synth.host_params(n, 21)
+    g = oracle.cast_bf16(synth.host_grads_f32(n, 3))
+    m0 = (synth.host_grads_f32(n, 4) * 0.1).astype(np.float32)
+    v0 = (synth.host_grads_f32(n, 5) ** 2).astype(np.float32)
+    hp = zc.hparams(step=3, **HP)
+
+    def run(sh):
+        bufs = []
+        for src, dt, k in ((p, torch.float32, sh[0]), (m0, torch.float32, sh[1]), (v0, torch.float32, sh[2]),
+                           (g, torch.int16, sh[3]), (np.zeros(n, np.uint16), torch.int16, sh[4])):
+            full = torch.full((n + 8,), 77, dtype=dt, device=DEV)
+            view = full[k:k + n]
+            view.copy_(dev_f32(src) if dt == torch.float32 else dev_u16(src))
+            bufs.append((full, view, k))
+        views = [b[1] for b in bufs]
+        zc.adam_step(views[0], views[1], views[2], views[3], zc.BF16, n, hp, bf16_out=views[4])
+        sync()
+        for i, (full, view, k) in enumerate(bufs):
+            if i != 3:
+                assert (full[:k] == 77).all() and (full[k + n:] == 77).all(), "wrote outside the range"
+        return [v.clone() for v in views]
+
+    ref = run((0, 0, 0, 0, 0))
+    got = run(shifts)
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
+    om, ov, oo = m0.copy(), v0.copy(), np.zeros(n, np.uint16)
+    op = p.copy()
+    oracle.adam_step(op, om, ov, g, step=3, bf16_out=oo, **HP)
+    assert_state_close(host_f32(got[0]), host_f32(got[1]), host_f32(got[2]), op, om, ov, tag=str(shifts), steps=1)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 9])
+def test_short_stretch_that_starts_off_boundary(n):
+    """Fewer elements than it takes to reach the next 16-byte boundary, and just more."""
+    gpu, cpu = run_both(n, 2, g_bf16=True, offset=1, seed=40 + n)
+    check(gpu, cpu, tag=f"short n={n}", steps=2)
+
+
 @pytest.mark.parametrize("arith", [0, 1, 2])
 @pytest.mark.parametrize("rows", [1, 2, 4])
 def test_every_kernel_variant(arith, rows):

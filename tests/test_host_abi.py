@@ -62,6 +62,10 @@ def test_adam_step_rejects_bad_arguments_without_a_gpu():
     assert _status(zc.adam_step, A, A + 64, A + 128, A + 193, zc.BF16, 8, hp, stream=0) == zc.ERR_ALIGNMENT
     assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, 8, hp, bf16_out=A + 257, stream=0) == zc.ERR_ALIGNMENT
     assert _status(zc.adam_step, A, A, A + 128, A + 192, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    # partial overlaps, not only equal pointers: m starts inside p; bf16_out ends inside g
+    assert _status(zc.adam_step, A, A + 16, A + 128, A + 192, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, 8, hp, bf16_out=A + 180, stream=0) == zc.ERR_INVALID_ARG
+    assert "overlap" in zc.last_error()
     assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, 7, 8, hp, stream=0) == zc.ERR_INVALID_ARG
     assert _status(zc.adam_step, A, A + 64, A + 128, A + 192, zc.F32, (1 << 40) + 1, hp, stream=0) == zc.ERR_UNSUPPORTED
     for bad in (dict(step=0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0),
