@@ -52,6 +52,8 @@ def _prepare(lib):
     lib.zco_adam_step.argtypes = [vp, vp, vp, vp, i32, i64, f32, f32, f32, f32, f32,
                                   f32, i64, i32, vp, i32]
     lib.zco_adam_step.restype = None
+    lib.zco_adam_step_f32.argtypes = lib.zco_adam_step.argtypes
+    lib.zco_adam_step_f32.restype = None
     lib.zco_cast_bf16.argtypes = [vp, vp, i64]
     lib.zco_cast_bf16.restype = None
     lib.zco_upcast_bf16.argtypes = [vp, vp, i64]
@@ -87,11 +89,12 @@ def _ptr(a):
 
 
 def adam_step(p, m, v, g, *, lr, beta1, beta2, eps, weight_decay, step,
-              grad_scale=1.0, mode=ADAMW, bf16_out=None, skip=False):
+              grad_scale=1.0, mode=ADAMW, bf16_out=None, skip=False, all_fp32=False):
     """In-place Adam(W) step over flat fp32 ``p, m, v``.
 
     ``g`` is float32 (values) or uint16 (bf16 bit patterns).  ``bf16_out`` is
-    an optional uint16 array that receives RNE(p_new).
+    an optional uint16 array that receives RNE(p_new).  ``all_fp32`` selects the
+    second-opinion build whose per-element intermediates are fp32 instead of double.
     """
     _f32(p, "p"), _f32(m, "m"), _f32(v, "v")
     n = p.size
@@ -112,11 +115,11 @@ def adam_step(p, m, v, g, *, lr, beta1, beta2, eps, weight_decay, step,
         if bf16_out.dtype != np.uint16 or bf16_out.size != n or not bf16_out.flags.c_contiguous:
             raise TypeError("bf16_out must be a contiguous uint16 array of length n")
         out_ptr = _ptr(bf16_out)
-    _load().zco_adam_step(_ptr(p), _ptr(m), _ptr(v), _ptr(g), is_bf16, n,
-                          float(np.float32(lr)), float(np.float32(beta1)),
-                          float(np.float32(beta2)), float(np.float32(eps)),
-                          float(np.float32(weight_decay)), float(np.float32(grad_scale)),
-                          int(step), int(mode), out_ptr, 1 if skip else 0)
+    fn = _load().zco_adam_step_f32 if all_fp32 else _load().zco_adam_step
+    fn(_ptr(p), _ptr(m), _ptr(v), _ptr(g), is_bf16, n,
+       float(np.float32(lr)), float(np.float32(beta1)), float(np.float32(beta2)),
+       float(np.float32(eps)), float(np.float32(weight_decay)), float(np.float32(grad_scale)),
+       int(step), int(mode), out_ptr, 1 if skip else 0)
 
 
 def adam_step_groups(p, m, v, g, *, ranges=(), lr, weight_decay, grad_scale=1.0,

@@ -135,6 +135,65 @@ void zco_adam_step(float *p, float *m, float *v, const void *g, int g_is_bf16,
 }
 
 /*
+ * The same step with every per-element intermediate in fp32 (each operation rounded to
+ * fp32, no fused multiply-add; built with contraction off).  A second opinion that tells
+ * "rounding" from "formula" when a kernel disagrees with zco_adam_step: a kernel that
+ * computes in fp32 should sit within a few ulp of this one, a wrong formula sits far from
+ * both.  The once-per-call scalars (bias corrections, 1 - lr*wd is not formed: the decay is
+ * taken as p - (lr*wd)*p) are computed in double and rounded to fp32 once.
+ * Pinned by staying within a few fp32 ulp of zco_adam_step and by the step-1 closed form.
+ */
+void zco_adam_step_f32(float *p, float *m, float *v, const void *g, int g_is_bf16,
+                       int64_t n, float lr_f, float beta1_f, float beta2_f,
+                       float eps_f, float wd_f, float grad_scale_f, int64_t step,
+                       int mode, uint16_t *bf16_out, int skip)
+{
+    if (skip != 0)
+        return;
+    const double bc1 = 1.0 - pow((double)beta1_f, (double)step);
+    const double bc2 = 1.0 - pow((double)beta2_f, (double)step);
+    const float step_size = (float)((double)lr_f / bc1);
+    const float inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+    const float one_minus_beta1 = (float)(1.0 - (double)beta1_f);
+    const float one_minus_beta2 = (float)(1.0 - (double)beta2_f);
+    const float lr_wd = (float)((double)lr_f * (double)wd_f);
+    const float *g32 = (const float *)g;
+    const uint16_t *g16 = (const uint16_t *)g;
+
+    for (int64_t i = 0; i < n; ++i) {
+        float gi = g_is_bf16 ? zco_bf16_to_f32(g16[i]) : g32[i];
+        gi = gi * grad_scale_f;
+        const float p_old = p[i];
+        if (mode == ZCO_ADAM_L2)
+            gi = gi + wd_f * p_old;
+
+        const float m_a = beta1_f * m[i];
+        const float m_b = one_minus_beta1 * gi;
+        m[i] = m_a + m_b;
+        const float v_a = beta2_f * v[i];
+        const float v_b = one_minus_beta2 * gi;
+        const float v_c = v_b * gi;
+        v[i] = v_a + v_c;
+
+        const float root = sqrtf(v[i]);
+        const float denom_a = root * inv_sqrt_bc2;
+        const float denom = denom_a + eps_f;
+        const float ratio = m[i] / denom;
+        const float delta = step_size * ratio;
+        float p_dec = p_old;
+        if (mode == ZCO_ADAMW) {
+            const float shrink = lr_wd * p_old;
+            p_dec = p_old - shrink;
+        }
+        const float p_new = p_dec - delta;
+        p[i] = p_new;
+
+        if (bf16_out)
+            bf16_out[i] = zco_rne_bf16(p_new);   /* p_new is the stored fp32 value */
+    }
+}
+
+/*
  * Sum of squares of the (upcast) gradient in double, and a flag that is 1
  * when any element is NaN or infinite.  The sum skips nothing: a non-finite
  * element makes the sum non-finite as IEEE says.

@@ -169,6 +169,40 @@ def test_every_kernel_variant(arith, rows):
             zc.tune_set(k, val)
 
 
+@pytest.mark.parametrize("arith", [0, 2])
+def test_kernel_arithmetic_against_both_oracle_builds(arith):
+    """The fp32 kernel variant sits next to the all-fp32 oracle build and the fp64 variant on
+    top of the double build; either one far from both would be a formula error, not rounding."""
+    n, steps = 1 << 17, 10
+    old = zc.tune_get("adam.arith")
+    try:
+        zc.tune_set("adam.arith", arith)
+        gpu, cpu64 = run_both(n, steps, g_bf16=True, seed=31)
+    finally:
+        zc.tune_set("adam.arith", old)
+    p32 = synth.host_params(n, 31)
+    m32, v32 = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for t in range(1, steps + 1):
+        g = oracle.cast_bf16(synth.host_grads_f32(n, t))
+        oracle.adam_step(p32, m32, v32, g, step=t, all_fp32=True, **HP)
+    lr = np.float32(HP["lr"])
+
+    def p_ulps(a, b):
+        return np.abs(a.astype(np.float64) - b) / np.spacing(np.maximum(np.abs(b), lr)).astype(np.float64)
+
+    to64, to32 = p_ulps(gpu[0], cpu64[0]), p_ulps(gpu[0], p32)
+    assert to64.max() <= 3 * steps + 2 and to32.max() <= 6 * steps + 4
+    if arith == 2:
+        # same arithmetic as the double build up to fused multiply-adds: m and v identical,
+        # p off by at most one rounding, and closer to the double build than the fp32 build is
+        assert np.array_equal(gpu[1], cpu64[1]) and np.array_equal(gpu[2], cpu64[2])
+        assert to64.max() <= 1.0 and to64.mean() < p_ulps(p32, cpu64[0]).mean()
+    else:
+        # fp32 kernel (with fused multiply-adds): on average nearer the fp32 build's error
+        # level than a formula slip would allow
+        assert to64.mean() <= 2.0 and to32.mean() <= 2.0
+
+
 def test_adam_l2_mode_and_grad_scale():
     gpu, cpu = run_both(40000, 4, g_bf16=True, mode=zc.ADAM_L2, grad_scale=0.37)
     check(gpu, cpu, tag="l2", steps=4, m_floor=0.37e-4)

@@ -496,3 +496,65 @@ def test_clip_scale_closed_forms():
     c = float(oracle.clip_scale(sq, 7.0))
     assert abs(np.sqrt(sq) * c - 7.0) < 1e-4
     assert np.isnan(oracle.clip_scale(np.nan, 1.0)) and oracle.clip_scale(np.inf, 1.0) == 0.0
+
+
+# ---- the all-fp32 second opinion ---------------------------------------------------
+
+def test_all_fp32_build_step1_closed_form():
+    """Its own pin: step 1 from zero state, delta p = -lr g / (|g| + eps), with fp32-sized slack
+    (four fp32 roundings on the lr-sized term, one on p)."""
+    n = 4096
+    p, m, v = fresh(n, seed=3)
+    p0 = p.copy()
+    g = (np.random.default_rng(4).standard_normal(n) * 1e-3).astype(np.float32)
+    hp = dict(HP, weight_decay=0.0)
+    oracle.adam_step(p, m, v, g, step=1, all_fp32=True, **hp)
+    lr, eps = float(np.float32(hp["lr"])), float(np.float32(hp["eps"]))
+    gd = g.astype(np.float64)
+    want = -lr * gd / (np.abs(gd) + eps)
+    delta = p.astype(np.float64) - p0.astype(np.float64)
+    half_ulp = 0.5 * np.spacing(np.maximum(np.abs(p0), np.abs(p))).astype(np.float64)
+    assert np.all(np.abs(delta - want) <= half_ulp + 6e-7 * lr)
+    b1, b2 = np.float32(0.9), np.float32(0.999)
+    omb1, omb2 = np.float32(1.0 - float(b1)), np.float32(1.0 - float(b2))
+    assert np.array_equal(m, omb1 * g)
+    assert np.array_equal(v, (omb2 * g) * g)
+
+
+@pytest.mark.parametrize("mode", [oracle.ADAMW, oracle.ADAM_L2])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_all_fp32_build_stays_within_a_few_ulp_of_the_double_build(mode, bf16):
+    n, steps = 20000, 10
+    pa, ma, va = fresh(n, seed=5)
+    pb, mb, vb = pa.copy(), ma.copy(), va.copy()
+    for t in range(1, steps + 1):
+        g = synth.host_grads_f32(n, t)
+        if bf16:
+            g = oracle.cast_bf16(g)
+        oracle.adam_step(pa, ma, va, g, step=t, mode=mode, **HP)
+        oracle.adam_step(pb, mb, vb, g, step=t, mode=mode, all_fp32=True, **HP)
+    lr = np.float32(HP["lr"])
+    # per step: sqrt, two products, one sum and the quotient round in fp32 on the lr-sized
+    # term, p rounds once more than in the double build
+    p_ulp = np.abs(pa.astype(np.float64) - pb) / np.spacing(np.maximum(np.abs(pa), lr)).astype(np.float64)
+    assert p_ulp.max() <= 3 * steps + 2
+    # v is a sum of positive terms: relative error grows by about an ulp per step
+    assert ulp_diff(va, vb).max() <= 2 * steps + 2
+    # m is a signed sum: ulp taken at the size of its terms
+    m_ulp = np.abs(ma.astype(np.float64) - mb) / np.spacing(np.maximum(np.abs(ma), np.float32(1e-4))).astype(np.float64)
+    assert m_ulp.max() <= 2 * steps + 2
+    # and the two builds are not the same code path: somewhere they differ in the last bit
+    assert (pa != pb).any() or (va != vb).any()
+
+
+def test_all_fp32_build_skip_and_fused_cast():
+    n = 1000
+    p, m, v = fresh(n, seed=6)
+    g = synth.host_grads_f32(n, 1)
+    keep = (p.copy(), m.copy(), v.copy())
+    out = np.full(n, 0xABCD, np.uint16)
+    oracle.adam_step(p, m, v, g, step=1, skip=True, bf16_out=out, all_fp32=True, **HP)
+    assert np.array_equal(p, keep[0]) and np.array_equal(m, keep[1]) and np.array_equal(v, keep[2])
+    assert (out == 0xABCD).all()
+    oracle.adam_step(p, m, v, g, step=1, bf16_out=out, all_fp32=True, **HP)
+    assert np.array_equal(out, oracle.cast_bf16(p))

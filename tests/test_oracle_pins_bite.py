@@ -48,6 +48,14 @@ MUTATIONS = {
     "clip_forgets_loss_scale": ("return (float)((double)inv_loss_scale * coef);", "return (float)coef;"),
     "accumulate_overwrites": ("acc[i] = (float)((double)acc[i] + gi * scale);",
                               "acc[i] = (float)(gi * scale);"),
+    # the all-fp32 second-opinion build
+    "f32_no_bias_correction_2": ("const float denom_a = root * inv_sqrt_bc2;", "const float denom_a = root;"),
+    "f32_wrong_sign": ("const float p_new = p_dec - delta;", "const float p_new = p_dec + delta;"),
+    "f32_v_without_square": ("const float v_c = v_b * gi;", "const float v_c = v_b;"),
+    "f32_eps_dropped": ("const float denom = denom_a + eps_f;", "const float denom = denom_a;"),
+    "f32_decay_dropped": ("p_dec = p_old - shrink;", "p_dec = p_old;"),
+    "f32_m_uses_beta2": ("const float m_a = beta1_f * m[i];", "const float m_a = beta2_f * m[i];"),
+    "f32_skip_ignored": ("    if (skip != 0)\n        return;", "    if (0)\n        return;"),
     "accumulate_ignores_scale": ("acc[i] = (float)((double)acc[i] + gi * scale);",
                                  "acc[i] = (float)((double)acc[i] + gi);"),
 }
@@ -63,6 +71,10 @@ PINS = [
     A.test_skip_touches_nothing_and_bf16_out_is_cast_of_p, A.test_nan_gradient_poisons_only_its_element,
     A.test_padding_stays_zero, A.test_grad_accumulate_closed_forms, A.test_clip_scale_closed_forms,
     A.test_groups_no_decay_range_and_lr_scale, A.test_offload_definition_is_concatenation, A.test_grad_sqnorm,
+    A.test_all_fp32_build_step1_closed_form,
+    lambda: A.test_all_fp32_build_stays_within_a_few_ulp_of_the_double_build(oracle.ADAMW, False),
+    lambda: A.test_all_fp32_build_stays_within_a_few_ulp_of_the_double_build(oracle.ADAM_L2, True),
+    A.test_all_fp32_build_skip_and_fused_cast,
     C.test_all_bf16_values_round_trip, C.test_every_tie_goes_to_even, C.test_special_values,
     C.test_nearest_value_property_on_random_bits, C.test_library_conversion_agrees,
     C.test_unshard_brute_force_ragged, C.test_unshard_hash_property_and_ranks_spanned,
