@@ -200,10 +200,14 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    def times(i):
+        return sorted(e[i].elapsed_time(e[i + 1]) for e in events)
+
     def avg(i):
-        return sum(e[i].elapsed_time(e[i + 1]) for e in events) / len(events)
+        return sum(times(i)) / len(events)
 
     t_norm, t_adam, t_unshard = avg(0), avg(1), avg(2)
+    spread = {"sqnorm": times(0), "adam": times(1), "unshard": times(2)}
     assert flag.item() == 0, "synthetic gradients must be finite"
 
     kernels = {}
@@ -257,7 +261,9 @@ def main():
                                                   "copy.waves_per_cu", "copy.nontemporal")},
         },
         "roofline": roofline,
-        "kernels": {k: dict(ms=round(d["ms"], 4), GBps=round(d["GBps"], 1), frac=round(d["frac"], 4),
+        "kernels": {k: dict(ms=round(d["ms"], 4), ms_median=round(spread[k][len(spread[k]) // 2], 4),
+                            ms_min=round(spread[k][0], 4),
+                            GBps=round(d["GBps"], 1), frac=round(d["frac"], 4),
                             algorithmic_bytes=d["bytes"],
                             rate_G_per_s=round(d["units"] / (d["ms"] * 1e-3) / 1e9, 2))
                     for k, d in kernels.items()},
