@@ -286,7 +286,7 @@ def main():
     if args.offload_elems > 0:
         legs = {}
         keep = zc.tune_get("offload.zero_copy")
-        for mode, name in ((1, "zero_copy"), (0, "staged_ring")):
+        for mode, name in ((1, "zero_copy"), (2, "staged_reads_direct_writes"), (0, "staged_ring")):
             zc.tune_set("offload.zero_copy", mode)
             legs[name] = offload_leg(torch, synth, zc, dev, args, probe=(mode == 0))
         zc.tune_set("offload.zero_copy", keep)

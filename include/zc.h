@@ -209,7 +209,7 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  * itself stays on the GPU).  Elements [0, n_resident) of the partition live
  * in DEVICE arrays p_dev/m_dev/v_dev; elements [n_resident, n_resident +
  * n_streamed) live in pinned HOST arrays p_host/m_host/v_host and cross the
- * host link once in each direction.  Two transports, chosen by the knob
+ * host link once in each direction.  Three transports, chosen by the knob
  * "offload.zero_copy" (results are bit-identical to zc_adam_step over the
  * concatenation either way):
  *   1 (default)  the update kernel reads and writes the pinned host arrays
@@ -221,6 +221,10 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  *                `hip_stream`, fenced by events.  With "offload.max_ahead" = 1
  *                (default) this transport blocks the calling thread while it
  *                feeds the ring; the results are still ordered on `hip_stream`.
+ *   2            staged reads, direct writes: chunks are copied host -> staging
+ *                slot on one internal stream, the kernel reads the slot and
+ *                stores the new state straight into the host arrays.  Same
+ *                host-blocking rule as 0.  Measured slower than 1.
  *
  * zc_offload_create   chunk_bytes: bytes per fp32 array per chunk, a positive
  *                     multiple of 4096 (64 MiB in the reference workload);
@@ -395,7 +399,8 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
  *   "copy.nontemporal"  non-temporal accesses in cast and unshard
  *   "launch.max_grid"  workgroups per launch (default 2^30); larger jobs are cut into
  *                      several launches
- *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default)
+ *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default),
+ *                      2 = staged reads + kernel writes pinned host
  *   "offload.zc_waves_per_cu"  resident-wave cap of the zero-copy kernel (0 = none)
  *   "offload.max_ahead" 1 (default) = the staged ring blocks the host so that it never runs
  *                      more than num_buffers chunks ahead of finished copy-backs (deep copy

@@ -136,10 +136,10 @@ __device__ __forceinline__ void st(T *ptr, T val)
 }
 
 template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH, bool GUARD>
-__device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restrict__ m4,
-                                          f32x4 *__restrict__ v4, const void *__restrict__ g,
-                                          u32x2 *__restrict__ out2, int64_t first, int64_t nvec,
-                                          const AdamScalars &s_in, DevCtl ctl)
+__device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, const f32x4 *v4,
+                                          f32x4 *po4, f32x4 *mo4, f32x4 *vo4,
+                                          const void *__restrict__ g, u32x2 *__restrict__ out2,
+                                          int64_t first, int64_t nvec, const AdamScalars &s_in, DevCtl ctl)
 {
     // The skip flag and the device-side scale are fetched together with the data and only
     // used after the tile's loads have been issued, so their latency hides behind them.
@@ -183,9 +183,9 @@ __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restr
                 mv[r][k] = me;
                 vv[r][k] = ve;
             }
-            st<NT>(p4 + i, pv[r]);
-            st<NT>(m4 + i, mv[r]);
-            st<NT>(v4 + i, vv[r]);
+            st<NT>(po4 + i, pv[r]);
+            st<NT>(mo4 + i, mv[r]);
+            st<NT>(vo4 + i, vv[r]);
             if (out2) {
                 u32x2 w;
                 w.x = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
@@ -200,26 +200,32 @@ __device__ __forceinline__ void adam_tile(f32x4 *__restrict__ p4, f32x4 *__restr
 // tile order, which keeps the set of pages the chip touches at any instant compact.
 // Requires p, m, v 16-byte aligned and g, out aligned to 4 elements.  `tile0` is the
 // tile index of workgroup 0 (launches are cut so that the grid stays below 2^31).
+// The new state goes to po, mo, vo: the same arrays for the in-place step, or other arrays
+// of the same alignment (the offloaded step reads staged copies and writes host memory).
+// Each element is read before it is written and by the same lane, so p == po needs no care.
 template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
-__global__ __launch_bounds__(BLOCK) void adam_vec_kernel(float *__restrict__ p, float *__restrict__ m,
-                                                         float *__restrict__ v,
+__global__ __launch_bounds__(BLOCK) void adam_vec_kernel(const float *p, const float *m, const float *v,
+                                                         float *po, float *mo, float *vo,
                                                          const void *__restrict__ g,
                                                          uint16_t *__restrict__ out, int64_t n,
                                                          int64_t tile0, AdamScalars s, DevCtl ctl)
 {
     const int64_t nvec = n >> 2;
-    f32x4 *p4 = reinterpret_cast<f32x4 *>(p);
-    f32x4 *m4 = reinterpret_cast<f32x4 *>(m);
-    f32x4 *v4 = reinterpret_cast<f32x4 *>(v);
+    const f32x4 *p4 = reinterpret_cast<const f32x4 *>(p);
+    const f32x4 *m4 = reinterpret_cast<const f32x4 *>(m);
+    const f32x4 *v4 = reinterpret_cast<const f32x4 *>(v);
+    f32x4 *po4 = reinterpret_cast<f32x4 *>(po);
+    f32x4 *mo4 = reinterpret_cast<f32x4 *>(mo);
+    f32x4 *vo4 = reinterpret_cast<f32x4 *>(vo);
     u32x2 *out2 = reinterpret_cast<u32x2 *>(out);
     constexpr int64_t kTileVecs = (int64_t)BLOCK * ROWS;
 
     const int64_t tile = tile0 + blockIdx.x;
     const int64_t first = tile * kTileVecs + threadIdx.x;
     if ((tile + 1) * kTileVecs <= nvec)
-        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false>(p4, m4, v4, g, out2, first, nvec, s, ctl);
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false>(p4, m4, v4, po4, mo4, vo4, g, out2, first, nvec, s, ctl);
     else
-        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true>(p4, m4, v4, g, out2, first, nvec, s, ctl);
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true>(p4, m4, v4, po4, mo4, vo4, g, out2, first, nvec, s, ctl);
 
     // The last n % 4 elements, one lane each, in the very first workgroup.
     const int64_t i = (nvec << 2) + threadIdx.x;
@@ -235,9 +241,9 @@ __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(float *__restrict__ p, 
         else
             ge = reinterpret_cast<const float *>(g)[i];
         adam_elem<ARITH>(pe, me, ve, ge, s);
-        p[i] = pe;
-        m[i] = me;
-        v[i] = ve;
+        po[i] = pe;
+        mo[i] = me;
+        vo[i] = ve;
         if (out)
             out[i] = (uint16_t)bf16_rne(pe);
     }
@@ -245,8 +251,8 @@ __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(float *__restrict__ p, 
 
 // Any natural alignment: one element per lane, grid-stride.
 template <bool G_BF16, int ARITH>
-__global__ __launch_bounds__(256) void adam_scalar_kernel(float *__restrict__ p, float *__restrict__ m,
-                                                          float *__restrict__ v,
+__global__ __launch_bounds__(256) void adam_scalar_kernel(const float *p, const float *m, const float *v,
+                                                          float *po, float *mo, float *vo,
                                                           const void *__restrict__ g,
                                                           uint16_t *__restrict__ out, int64_t n,
                                                           AdamScalars s, DevCtl ctl)
@@ -266,9 +272,9 @@ __global__ __launch_bounds__(256) void adam_scalar_kernel(float *__restrict__ p,
         else
             ge = reinterpret_cast<const float *>(g)[i];
         adam_elem<ARITH>(pe, me, ve, ge, s);
-        p[i] = pe;
-        m[i] = me;
-        v[i] = ve;
+        po[i] = pe;
+        mo[i] = me;
+        vo[i] = ve;
         if (out)
             out[i] = (uint16_t)bf16_rne(pe);
     }
@@ -278,7 +284,8 @@ struct VecLaunch {
     dim3 grid;
     size_t lds;
     hipStream_t stream;
-    float *p, *m, *v;
+    const float *p, *m, *v;
+    float *po, *mo, *vo;
     const void *g;
     uint16_t *out;
     int64_t n, tile0;
@@ -290,7 +297,8 @@ template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
 static void launch_vec(const VecLaunch &a)
 {
     hipLaunchKernelGGL((adam_vec_kernel<ROWS, BLOCK, G_BF16, NT, ARITH>), a.grid, dim3(BLOCK), a.lds,
-                       a.stream, a.p, a.m, a.v, a.g, a.out, a.n, a.tile0, a.s, a.ctl);
+                       a.stream, a.p, a.m, a.v, a.po, a.mo, a.vo, a.g, a.out, a.n, a.tile0, a.s,
+                       a.ctl);
 }
 
 template <int ROWS, int BLOCK, bool G_BF16, bool NT>
@@ -324,7 +332,8 @@ static void pick_rows(int rows, bool g_bf16, bool nt, int arith, const VecLaunch
     else pick_flags<4, BLOCK>(g_bf16, nt, arith, a);
 }
 
-static void launch_scalar(float *p, float *m, float *v, const void *g, bool g_bf16, int64_t n,
+static void launch_scalar(const float *p, const float *m, const float *v, float *po, float *mo, float *vo,
+                          const void *g, bool g_bf16, int64_t n,
                           uint16_t *bf16_out, const AdamScalars &s, DevCtl ctl, int arith, int cus,
                           hipStream_t stream)
 {
@@ -334,8 +343,8 @@ static void launch_scalar(float *p, float *m, float *v, const void *g, bool g_bf
         blocks = cap;
     const dim3 grid((unsigned)blocks);
 #define ZC_SCALAR(GB, AR)                                                                             \
-    hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, g, bf16_out, \
-                       n, s, ctl)
+    hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, po, mo, vo, \
+                       g, bf16_out, n, s, ctl)
     if (g_bf16) {
         if (arith == 0) ZC_SCALAR(true, 0);
         else if (arith == 1) ZC_SCALAR(true, 1);
@@ -350,11 +359,15 @@ static void launch_scalar(float *p, float *m, float *v, const void *g, bool g_bf
 
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
-                      hipStream_t stream, int waves_per_cu, const float *grad_scale_dev)
+                      hipStream_t stream, int waves_per_cu, const float *grad_scale_dev,
+                      const AdamOut *out_of_place)
 {
     const DevCtl ctl{skip_flag, grad_scale_dev};
     if (n == 0)
         return ZC_OK;
+    float *po = out_of_place ? out_of_place->p : p;
+    float *mo = out_of_place ? out_of_place->m : m;
+    float *vo = out_of_place ? out_of_place->v : v;
     const AdamScalars s = make_scalars(hp);
     const Tune &t = tune();
     const bool g_bf16 = g_dtype == ZC_BF16;
@@ -374,6 +387,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
     auto vec_ok_after = [&](int64_t k) {
         const char *gk = static_cast<const char *>(g) + k * g_size;
         return k < n && aligned_to(p + k, 16) && aligned_to(m + k, 16) && aligned_to(v + k, 16) &&
+               aligned_to(po + k, 16) && aligned_to(mo + k, 16) && aligned_to(vo + k, 16) &&
                aligned_to(gk, g_bf16 ? 8 : 16) && (!bf16_out || aligned_to(bf16_out + k, 8));
     };
     int64_t peel = -1;                     // -1: the whole stretch takes the scalar kernel
@@ -388,13 +402,16 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
     if (peel != 0)
         ZC_TRY(num_cus(&cus));
     if (peel < 0) {
-        launch_scalar(p, m, v, g, g_bf16, n, bf16_out, s, ctl, arith, cus, stream);
+        launch_scalar(p, m, v, po, mo, vo, g, g_bf16, n, bf16_out, s, ctl, arith, cus, stream);
     } else {
         if (peel > 0) {
-            launch_scalar(p, m, v, g, g_bf16, peel, bf16_out, s, ctl, arith, cus, stream);
+            launch_scalar(p, m, v, po, mo, vo, g, g_bf16, peel, bf16_out, s, ctl, arith, cus, stream);
             p += peel;
             m += peel;
             v += peel;
+            po += peel;
+            mo += peel;
+            vo += peel;
             g = static_cast<const char *>(g) + peel * g_size;
             if (bf16_out)
                 bf16_out += peel;
@@ -408,7 +425,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds(waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu, block, &lds));
-        VecLaunch a{dim3(1), lds, stream, p, m, v, g, bf16_out, n, 0, s, ctl};
+        VecLaunch a{dim3(1), lds, stream, p, m, v, po, mo, vo, g, bf16_out, n, 0, s, ctl};
         const int64_t kMaxGrid = t.launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;

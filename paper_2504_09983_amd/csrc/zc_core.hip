@@ -136,7 +136,7 @@ static const Knob kKnobs[] = {
     {"accum.waves_per_cu", &Tune::accum_waves_per_cu, 0, 64},
     {"copy.nontemporal", &Tune::copy_nontemporal, 0, 1},
     {"launch.max_grid", &Tune::launch_max_grid, 1, int64_t(1) << 30},
-    {"offload.zero_copy", &Tune::offload_zero_copy, 0, 1},
+    {"offload.zero_copy", &Tune::offload_zero_copy, 0, 2},
     {"offload.zc_waves_per_cu", &Tune::offload_zc_waves_per_cu, 0, 64},
     {"offload.max_ahead", &Tune::offload_max_ahead, 0, 1},
     {"offload.d2h_on_compute", &Tune::offload_d2h_on_compute, 0, 1},

@@ -38,7 +38,7 @@ struct Tune {
     int64_t accum_waves_per_cu = 24;
     int64_t copy_nontemporal = 1;
     int64_t launch_max_grid = int64_t(1) << 30;
-    int64_t offload_zero_copy = 1;
+    int64_t offload_zero_copy = 1;   // 0 staged ring, 1 zero-copy kernel, 2 staged reads + direct writes
     int64_t offload_zc_waves_per_cu = 0;
     int64_t offload_max_ahead = 1;
     int64_t offload_d2h_on_compute = 0;
@@ -60,9 +60,15 @@ zc_status check_dtype(zc_dtype t);
 // Enqueue the fused update over n elements; arguments already validated.
 // waves_per_cu < 0 takes the "adam.waves_per_cu" knob, otherwise overrides it.
 // grad_scale_dev (DEVICE, may be NULL) multiplies hp->grad_scale at execution time.
+// out_of_place (may be NULL): the new p, m, v go to these arrays instead of back into
+// p, m, v, which are then only read.
+struct AdamOut {
+    float *p, *m, *v;
+};
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
-                      hipStream_t stream, int waves_per_cu = -1, const float *grad_scale_dev = nullptr);
+                      hipStream_t stream, int waves_per_cu = -1, const float *grad_scale_dev = nullptr,
+                      const AdamOut *out_of_place = nullptr);
 
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

@@ -5,7 +5,7 @@
 // asynchronously so that transfers overlap with computation, memory is only
 // reused after the copy has completed, and the update itself runs on the GPU.
 //
-// Two transports are built.
+// Three transports are built.
 //
 // Zero-copy (default): the fused update kernel is pointed at the pinned host
 // arrays.  Its 128-bit loads become link reads, its stores link writes, both
@@ -17,6 +17,11 @@
 //   h2d stream : wait(slot free) -> 3 x hipMemcpyAsync host->slot -> record(loaded)
 //   caller's   : wait(loaded)    -> fused update kernel on slot   -> record(updated)
 //   d2h stream : wait(updated)   -> 3 x hipMemcpyAsync slot->host -> record(slot free)
+//
+// Staged reads, direct writes: the h2d stream of the ring feeds the slots, the update
+// kernel reads a slot and stores the new state straight into the host arrays (no
+// copy-back stream).  Measured 43 GB/s each way against 46 for zero-copy: kept as a
+// measured alternative, not the default.
 //
 // Measured on MI355X the ring reaches the plain-memcpy ceiling of the link when
 // the caller synchronises between steps.  The runtime executes the copy-backs as
@@ -298,7 +303,7 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
     const char *g_tail = static_cast<const char *>(g_dev) + n_resident * g_size;
     uint16_t *out_tail = bf16_out_dev ? bf16_out_dev + n_resident : nullptr;
 
-    if (tune().offload_zero_copy) {
+    if (tune().offload_zero_copy == 1) {
         // The update kernel itself reads and writes the pinned host arrays through the
         // link: no staging, no copy engines, one launch.  The link is the bound, so the
         // HBM-motivated cap on resident waves is lifted (more requests in flight).
@@ -318,6 +323,44 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
     const int64_t ce = ctx->chunk_elems;
     const int nb = ctx->num_buffers;
     const int64_t nchunks = (n_streamed + ce - 1) / ce;
+
+    if (tune().offload_zero_copy == 2) {
+        // Staged reads, direct writes: a copy engine brings each chunk into a ring slot
+        // (large read requests on the link), the update kernel reads the slot from HBM and
+        // stores the new state straight into the pinned host arrays.  Nothing is copied
+        // back by the runtime, so only two streams take part and a slot is free again as
+        // soon as its kernel has finished.
+        float *pd = nullptr, *md = nullptr, *vd = nullptr;
+        ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&pd), p_host, 0));
+        ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&md), m_host, 0));
+        ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&vd), v_host, 0));
+        for (int64_t k = 0; k < nchunks; ++k) {
+            const int slot = (int)(k % nb);
+            const int64_t off = k * ce;
+            const int64_t cnt = (n_streamed - off) < ce ? (n_streamed - off) : ce;
+            const size_t bytes = (size_t)cnt * 4;
+            float *sp = ctx->staging + (int64_t)slot * 3 * ce;
+            float *sm = sp + ce;
+            float *sv = sm + ce;
+            if (k >= nb) {
+                if (tune().offload_max_ahead > 0)
+                    ZC_HIP(hipEventSynchronize(ctx->freed[slot]));
+                ZC_HIP(hipStreamWaitEvent(ctx->h2d, ctx->freed[slot], 0));
+            }
+            ZC_HIP(hipMemcpyAsync(sp, p_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
+            ZC_HIP(hipMemcpyAsync(sm, m_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
+            ZC_HIP(hipMemcpyAsync(sv, v_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
+            ZC_HIP(hipEventRecord(ctx->loaded[slot], ctx->h2d));
+
+            ZC_HIP(hipStreamWaitEvent(stream, ctx->loaded[slot], 0));
+            const AdamOut to_host{pd + off, md + off, vd + off};
+            ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp,
+                               out_tail ? out_tail + off : nullptr, skip_flag, stream,
+                               (int)tune().offload_zc_waves_per_cu, nullptr, &to_host));
+            ZC_HIP(hipEventRecord(ctx->freed[slot], stream));
+        }
+        return ZC_OK;
+    }
     for (int64_t k = 0; k < nchunks; ++k) {
         const int slot = (int)(k % nb);
         const int64_t off = k * ce;

@@ -35,7 +35,7 @@ def offload_vs_resident(n, n_res, chunk_bytes, nbuf, steps=2, g_bf16=True, zero_
 
     ctx = zc.offload_create(chunk_bytes, nbuf)
     old = zc.tune_get("offload.zero_copy")
-    zc.tune_set("offload.zero_copy", 1 if zero_copy else 0)
+    zc.tune_set("offload.zero_copy", int(zero_copy))   # 0 ring, 1 zero-copy, 2 staged reads + direct writes
     try:
         for t in range(1, steps + 1):
             g = synth.host_grads_f32(n, t)
@@ -64,7 +64,7 @@ def offload_vs_resident(n, n_res, chunk_bytes, nbuf, steps=2, g_bf16=True, zero_
     assert np.array_equal(host_u16(oout), oracle.cast_bf16(host_f32(rp)))
 
 
-@pytest.mark.parametrize("zero_copy", [False, True])
+@pytest.mark.parametrize("zero_copy", [0, 1, 2])
 @pytest.mark.parametrize("frac", [0.0, 0.25, 0.5, 1.0])
 def test_offload_equals_resident_fractions(frac, zero_copy):
     n = 3 * (1 << 20) + 4099
@@ -72,12 +72,13 @@ def test_offload_equals_resident_fractions(frac, zero_copy):
     offload_vs_resident(n, n_res, 1 << 20, 3, zero_copy=zero_copy)
 
 
+@pytest.mark.parametrize("transport", [0, 2])
 @pytest.mark.parametrize("nbuf", [1, 2, 3, 5])
 @pytest.mark.parametrize("chunk_bytes", [4096, 1 << 16])
-def test_offload_ring_sizes(nbuf, chunk_bytes):
+def test_offload_ring_sizes(nbuf, chunk_bytes, transport):
     # many chunks through few slots: every slot is reused several times
     n = 40 * (chunk_bytes // 4) // 3 + 17
-    offload_vs_resident(n, 1024, chunk_bytes, nbuf, steps=2)
+    offload_vs_resident(n, 1024, chunk_bytes, nbuf, steps=2, zero_copy=transport)
 
 
 def test_offload_fp32_grads_and_single_partial_chunk():
@@ -89,6 +90,7 @@ def test_offload_64mib_chunks():
     """The reference chunk size: 64 MiB per array, 3 slots, 2.5 chunks."""
     n = (16 << 20) * 2 + (8 << 20) + 5
     offload_vs_resident(n, 0, 64 << 20, 3, steps=1)
+    offload_vs_resident(n, 0, 64 << 20, 3, steps=1, zero_copy=2)
 
 
 def test_offload_zero_copy_mode():
@@ -106,7 +108,7 @@ def test_offload_zero_copy_mode():
     ctx = zc.offload_create(1 << 16, 2)
     old = zc.tune_get("offload.zero_copy")
     try:
-        for mode in (1, 0):
+        for mode in (1, 0, 2):
             zc.tune_set("offload.zero_copy", mode)
             for b in base:
                 b.zero_()
@@ -156,3 +158,34 @@ def test_resume_after_round_trip_through_host():
     sync()
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("transport", [0, 1, 2])
+def test_offload_skip_flag_leaves_host_and_device_state_untouched(transport):
+    n, n_res = (1 << 19) + 13, 4096
+    p0, m0, v0 = synth.host_params(n, 71), synth.host_normal(n, 1e-4, 72), np.abs(synth.host_normal(n, 1e-7, 73))
+    dp, dm, dv = dev_f32(p0[:n_res]), dev_f32(m0[:n_res]), dev_f32(v0[:n_res])
+    hp_, hm_, hv_ = pinned(p0[n_res:]), pinned(m0[n_res:]), pinned(v0[n_res:])
+    dg = dev_u16(oracle.cast_bf16(synth.host_grads_f32(n, 1)))
+    out = torch.full((n,), 0x3C3C, dtype=torch.int16, device=DEV)
+    flag = torch.ones(1, dtype=torch.int32, device=DEV)
+    ctx = zc.offload_create(1 << 18, 2)
+    old = zc.tune_get("offload.zero_copy")
+    zc.tune_set("offload.zero_copy", transport)
+    try:
+        ctx.adam_step(dp, dm, dv, n_res, hp_, hm_, hv_, n - n_res, dg, zc.BF16, zc.hparams(step=1, **HP),
+                      bf16_out_dev=out, skip_flag=flag)
+        sync()
+        for host, dev, ref in ((hp_, dp, p0), (hm_, dm, m0), (hv_, dv, v0)):
+            assert np.array_equal(host.numpy().view(np.uint32), ref[n_res:].view(np.uint32))
+            assert np.array_equal(host_f32(dev).view(np.uint32), ref[:n_res].view(np.uint32))
+        assert (out == 0x3C3C).all()
+        # and with the flag cleared the same call does the step
+        flag.zero_()
+        ctx.adam_step(dp, dm, dv, n_res, hp_, hm_, hv_, n - n_res, dg, zc.BF16, zc.hparams(step=1, **HP),
+                      bf16_out_dev=out, skip_flag=flag)
+        sync()
+        assert not np.array_equal(hp_.numpy(), p0[n_res:]) and (out != 0x3C3C).any()
+    finally:
+        zc.tune_set("offload.zero_copy", old)
+        ctx.destroy()
