@@ -106,14 +106,18 @@ struct SegDesc {
     int64_t first_tile;
 };
 
-__device__ __forceinline__ u32x4 load_src_vec(const uint16_t *s, unsigned align_class, bool nt)
+// align_class: 0 = source 16-byte aligned, 1 = 4-byte aligned, 2 = 2-byte aligned.
+template <int ALIGN, bool NT>
+__device__ __forceinline__ u32x4 load_src_vec(const uint16_t *s)
 {
-    // align_class: 0 = 16-byte aligned, 1 = 4-byte aligned, 2 = 2-byte aligned
     u32x4 w;
-    if (align_class == 0) {
+    if constexpr (ALIGN == 0) {
         const u32x4 *q = reinterpret_cast<const u32x4 *>(s);
-        w = nt ? __builtin_nontemporal_load(q) : *q;
-    } else if (align_class == 1) {
+        if constexpr (NT)
+            w = __builtin_nontemporal_load(q);
+        else
+            w = *q;
+    } else if constexpr (ALIGN == 1) {
         const uint32_t *q = reinterpret_cast<const uint32_t *>(s);
         w.x = q[0];
         w.y = q[1];
@@ -126,6 +130,30 @@ __device__ __forceinline__ u32x4 load_src_vec(const uint16_t *s, unsigned align_
         w.w = (uint32_t)s[6] | ((uint32_t)s[7] << 16);
     }
     return w;
+}
+
+// One tile of the aligned body: every load of the tile is issued before the first store.
+// The alignment class is the same for the whole wave, so the caller branches once and the
+// loads of a tile issue back to back (with the class tested per load the compiler waited
+// after each of them).  The per-vector bounds test stays on full tiles as well: a variant
+// without it measured 2.7 % slower.
+template <int ALIGN, bool NT>
+__device__ __forceinline__ void copy_tile(const uint16_t *sb, u32x4 *db, int64_t t, int64_t body_vecs)
+{
+    const int64_t first = t * kTileVecs + threadIdx.x;
+    u32x4 w[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        const int64_t i = first + k * kCopyBlock;
+        if (i < body_vecs)
+            w[k] = load_src_vec<ALIGN, NT>(sb + (i << 3));
+    }
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        const int64_t i = first + k * kCopyBlock;
+        if (i < body_vecs)
+            stc<NT>(db + i, w[k]);
+    }
 }
 
 constexpr int kHintShift = 10;  // one hint per 1024 tiles
@@ -177,22 +205,12 @@ __global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const uint16_t *__r
         const uint16_t *sb = src + head;
         u32x4 *db = reinterpret_cast<u32x4 *>(dst + head);
         const uintptr_t sa = reinterpret_cast<uintptr_t>(sb);
-        const unsigned align_class = (sa & 15u) == 0 ? 0u : ((sa & 3u) == 0 ? 1u : 2u);
-
-        const int64_t first = t * kTileVecs + threadIdx.x;
-        u32x4 w[kUnroll];
-#pragma unroll
-        for (int k = 0; k < kUnroll; ++k) {
-            const int64_t i = first + k * kCopyBlock;
-            if (i < body_vecs)
-                w[k] = load_src_vec(sb + (i << 3), align_class, NT);
-        }
-#pragma unroll
-        for (int k = 0; k < kUnroll; ++k) {
-            const int64_t i = first + k * kCopyBlock;
-            if (i < body_vecs)
-                stc<NT>(db + i, w[k]);
-        }
+        if ((sa & 15u) == 0)
+            copy_tile<0, NT>(sb, db, t, body_vecs);
+        else if ((sa & 3u) == 0)
+            copy_tile<1, NT>(sb, db, t, body_vecs);
+        else
+            copy_tile<2, NT>(sb, db, t, body_vecs);
     }
 }
 
