@@ -80,7 +80,7 @@ def total_params(shape: ModelShape) -> int:
 TINY_TENSORS = [(f"w{i}", (512, 512)) for i in range(4)]  # 1,048,576 elements
 TINY_N = 4 * 512 * 512
 
-# Hyper-parameters of every BASELINE configuration.
+# Hyper-parameters of every benchmark workload.
 HP = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
 P_STD = 0.02
 G_STD = 1e-3

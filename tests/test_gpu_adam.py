@@ -69,7 +69,7 @@ def check(gpu, cpu, with_out=True, tag="", steps=10, m_floor=1e-4):
 
 
 def test_tiny_config_ten_steps_fp32_grads():
-    """BASELINE config 1: n = 2^20, fp32 grads, 10 AdamW steps."""
+    """Tiny workload: n = 2^20, fp32 grads, 10 AdamW steps."""
     n = synth.TINY_N
     gpu, cpu = run_both(n, 10, g_bf16=False)
     check(gpu, cpu, tag="cfg1")

@@ -126,7 +126,7 @@ def run_unshard(numels, world=8, align=8, dst_shift=None, src_shift=0, tune=None
 
 
 def test_tiny_config_unshard_four_matrices():
-    """BASELINE config 1: 2^20 elements -> 4 tensors of 512 x 512 (fed by the step's bf16 copy)."""
+    """Tiny workload: 2^20 elements -> 4 tensors of 512 x 512 (fed by the step's bf16 copy)."""
     n = synth.TINY_N
     p = synth.host_params(n, 1)
     bits = oracle.cast_bf16(p)

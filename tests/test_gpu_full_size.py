@@ -1,4 +1,4 @@
-"""GPU parity at the full BASELINE sizes, in the launch configuration the
+"""GPU parity at the full benchmark sizes, in the launch configuration the
 benchmark times.  Inputs are generated on the GPU; windows of them are copied to
 the host and fed to the oracle, and properties that hold at any size (index-hash
 identity of the unshard copy, fused cast == RNE of the stored p) cover the rest."""
@@ -59,7 +59,7 @@ def run_windowed(n, steps, with_out, wins):
 
 
 def test_llama8b_shard_ten_steps():
-    """BASELINE config 2: n = 1,003,782,656, bf16 grads, all resident, 10 steps, no cast."""
+    """Llama-3-8B one-of-8 shard: n = 1,003,782,656, bf16 grads, all resident, 10 steps, no cast."""
     _, shard, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_8B), 8, 1)
     assert shard == 1_003_782_656
     wins = windows_for(shard, seed=2)
@@ -71,7 +71,7 @@ def test_llama8b_shard_ten_steps():
 
 
 def test_llama70b_shard_step_and_cast():
-    """BASELINE config 3: n = 8,819,213,312 (p/m/v ~105 GB resident), fused bf16 copy."""
+    """Llama-3-70B one-of-8 shard: n = 8,819,213,312 (p/m/v ~105 GB resident), fused bf16 copy."""
     _, shard, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_70B), 8, 1)
     assert shard == 8_819_213_312
     wins = windows_for(shard, extra_boundaries=[shard // 2], seed=3)
@@ -121,7 +121,7 @@ def test_llama70b_shard_every_element_after_step_one():
 
 
 def test_mixtral_unshard_full_size():
-    """BASELINE config 5: gathered flat bf16 buffer of 8 rank shards (rank-padded) unsharded
+    """Mixtral-8x7B: gathered flat bf16 buffer of 8 rank shards (rank-padded) unsharded
     into 995 separately allocated tensors; bit-exact layout check by index hash."""
     shape = synth.MIXTRAL_8X7B
     tensors = synth.tensor_list(shape)
