@@ -140,6 +140,7 @@ static const Knob kKnobs[] = {
     {"offload.zc_waves_per_cu", &Tune::offload_zc_waves_per_cu, 0, 64},
     {"offload.max_ahead", &Tune::offload_max_ahead, 0, 1},
     {"offload.d2h_on_compute", &Tune::offload_d2h_on_compute, 0, 1},
+    {"offload.poison", &Tune::offload_poison, 0, 1},
 };
 
 static const Knob *find_knob(const char *key)

@@ -42,6 +42,7 @@ struct Tune {
     int64_t offload_zc_waves_per_cu = 0;
     int64_t offload_max_ahead = 1;
     int64_t offload_d2h_on_compute = 0;
+    int64_t offload_poison = 0;      // overwrite every ring slot once its chunk has left it
 };
 Tune &tune();
 
@@ -69,6 +70,9 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
                       hipStream_t stream, int waves_per_cu = -1, const float *grad_scale_dev = nullptr,
                       const AdamOut *out_of_place = nullptr);
+
+// Fill `words` 32-bit words at dst (DEVICE) with 0xDEADBEEF on `stream`.
+zc_status launch_poison(void *dst, int64_t words, hipStream_t stream);
 
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

@@ -357,6 +357,8 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
             ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp,
                                out_tail ? out_tail + off : nullptr, skip_flag, stream,
                                (int)tune().offload_zc_waves_per_cu, nullptr, &to_host));
+            if (tune().offload_poison)
+                ZC_TRY(launch_poison(sp, 3 * ce, stream));
             ZC_HIP(hipEventRecord(ctx->freed[slot], stream));
         }
         return ZC_OK;
@@ -395,6 +397,8 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
         ZC_HIP(hipMemcpyAsync(p_host + off, sp, bytes, hipMemcpyDeviceToHost, back));
         ZC_HIP(hipMemcpyAsync(m_host + off, sm, bytes, hipMemcpyDeviceToHost, back));
         ZC_HIP(hipMemcpyAsync(v_host + off, sv, bytes, hipMemcpyDeviceToHost, back));
+        if (tune().offload_poison)
+            ZC_TRY(launch_poison(sp, 3 * ce, back));
         ZC_HIP(hipEventRecord(ctx->freed[slot], back));
     }
 

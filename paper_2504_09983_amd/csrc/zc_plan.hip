@@ -47,6 +47,23 @@ __global__ __launch_bounds__(256) void poison_kernel(uint32_t *__restrict__ dst,
         dst[i] = 0xDEADBEEFu;
 }
 
+// Overwrite `words` 32-bit words with a pattern no optimizer state holds: stands in for
+// handing memory to another owner, so that a missing fence shows up as garbage.
+zc_status launch_poison(void *dst, int64_t words, hipStream_t stream)
+{
+    if (words <= 0)
+        return ZC_OK;
+    int cus = 0;
+    ZC_TRY(num_cus(&cus));
+    int64_t blocks = (words + 255) / 256;
+    if (blocks > (int64_t)cus * 8)
+        blocks = (int64_t)cus * 8;
+    hipLaunchKernelGGL(poison_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<uint32_t *>(dst), words);
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
+}
+
 // Profiled communication time for `bytes`: the table is linear between samples, flat
 // below the first one and continued with the last slope above the last one.
 static double comm_time(int64_t bytes, const int64_t *sizes, const double *times, int64_t n)
@@ -382,8 +399,6 @@ zc_status zc_schedule_run(zc_offload_ctx *ctx, const zc_sched_op *ops, int64_t n
     ZC_HIP(hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev));
     if (clock_khz <= 0)
         clock_khz = 100000;
-    int cus = 0;
-    ZC_TRY(num_cus(&cus));
 
     hipStream_t stream = (hipStream_t)hip_stream;
     hipStream_t h2d = offload_h2d_stream(ctx), d2h = offload_d2h_stream(ctx);
@@ -415,16 +430,8 @@ zc_status zc_schedule_run(zc_offload_ctx *ctx, const zc_sched_op *ops, int64_t n
             break;
         case ZC_OP_SYNC_FREE:
             ZC_HIP(hipStreamWaitEvent(stream, ev[idx], 0));
-            if (poison_freed && frags[idx].bytes > 0) {
-                // stands in for handing the memory to someone else
-                const int64_t words = frags[idx].bytes / 4;
-                int64_t blocks = (words + 255) / 256;
-                if (blocks > (int64_t)cus * 8)
-                    blocks = (int64_t)cus * 8;
-                hipLaunchKernelGGL(poison_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                                   static_cast<uint32_t *>(frags[idx].dev), words);
-                ZC_HIP(hipGetLastError());
-            }
+            if (poison_freed)
+                ZC_TRY(launch_poison(frags[idx].dev, frags[idx].bytes / 4, stream));
             break;
         case ZC_OP_RELOAD:
             ZC_HIP(hipEventRecord(ev[3 * nfrags + idx], stream));

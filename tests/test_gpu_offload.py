@@ -189,3 +189,21 @@ def test_offload_skip_flag_leaves_host_and_device_state_untouched(transport):
     finally:
         zc.tune_set("offload.zero_copy", old)
         ctx.destroy()
+
+
+@pytest.mark.parametrize("transport", [0, 2])
+@pytest.mark.parametrize("nbuf", [1, 2, 3])
+def test_ring_slots_poisoned_after_use_change_nothing(transport, nbuf):
+    """Every slot is overwritten with garbage as soon as its chunk has left it; with all
+    fences in place the next chunk's copy lands after that and no result bit changes."""
+    old = {k: zc.tune_get(k) for k in ("offload.poison", "offload.max_ahead")}
+    try:
+        for ahead in (1, 0):
+            zc.tune_set("offload.poison", 1)
+            zc.tune_set("offload.max_ahead", ahead)
+            chunk = 1 << 16
+            n = 25 * (chunk // 4) + 333
+            offload_vs_resident(n, 2048, chunk, nbuf, steps=2, zero_copy=transport)
+    finally:
+        for k, val in old.items():
+            zc.tune_set(k, val)
