@@ -390,7 +390,8 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
  *   "adam.rows"        128-bit vectors per lane per tile: 1, 2 or 4
  *   "adam.block"       threads per workgroup: 64, 128 or 256
  *   "adam.waves_per_cu" cap on resident waves per compute unit, enforced through an
- *                      unused dynamic-LDS request; 0 = no cap
+ *                      unused dynamic-LDS request; 0 = no cap; -1 (default) = 12 with
+ *                      bf16 gradients and the fused bf16 copy, 10 otherwise
  *   "adam.nontemporal" 0/1 non-temporal loads and stores
  *   "adam.arith"       0 = fp32 only, 1 = fp64 multiply-adds with fp32 sqrt/div,
  *                      2 = fp64 throughout

@@ -424,7 +424,13 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
         if (ntiles == 0)
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
-        ZC_TRY(occupancy_cap_lds(waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu, block, &lds));
+        // Resident-wave cap: the caller's, else the knob's, else (knob at -1) what measured
+        // best per variant: 12 waves per CU with bf16 gradients and the fused bf16 copy,
+        // 10 for the other three combinations.
+        int cap = waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu;
+        if (cap < 0)
+            cap = (g_bf16 && bf16_out) ? 12 : 10;
+        ZC_TRY(occupancy_cap_lds(cap, block, &lds));
         VecLaunch a{dim3(1), lds, stream, p, m, v, po, mo, vo, g, bf16_out, n, 0, s, ctl};
         const int64_t kMaxGrid = t.launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {

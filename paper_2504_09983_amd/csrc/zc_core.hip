@@ -128,7 +128,7 @@ struct Knob {
 static const Knob kKnobs[] = {
     {"adam.rows", &Tune::adam_rows, 1, 4},
     {"adam.block", &Tune::adam_block, 64, 256},
-    {"adam.waves_per_cu", &Tune::adam_waves_per_cu, 0, 64},
+    {"adam.waves_per_cu", &Tune::adam_waves_per_cu, -1, 64},
     {"adam.nontemporal", &Tune::adam_nontemporal, 0, 1},
     {"adam.arith", &Tune::adam_arith, 0, 2},
     {"copy.waves_per_cu", &Tune::copy_waves_per_cu, 0, 64},
