@@ -442,3 +442,53 @@ def test_whole_step_replays_from_a_hip_graph():
         # interleave unrelated eager work and a sync between replays
         _ = (state[0] * 2).sum().item()
     plan.destroy()
+
+
+@pytest.mark.parametrize("arith", [2, 1, 0])
+@pytest.mark.parametrize("mode", [zc.ADAMW, zc.ADAM_L2])
+@pytest.mark.parametrize("eps", [1e-8, 0.0])
+def test_extreme_magnitudes_one_step(mode, eps, arith):
+    """Every combination of extreme p, g, m, v (zeros of both signs, subnormals, values whose
+    square overflows or underflows fp32, the largest finite numbers): the same class of result
+    (NaN, +-inf, zero) as the oracle and the usual bars on everything finite."""
+    ps = np.array([0.0, -0.0, 1e-39, -1.0, 0.02, 3e38, -3e38], np.float32)
+    gs = np.array([0.0, -0.0, 1e-45, -1e-30, 1e-20, -1e-3, 1.0, 1e19, -1e30, 3e38], np.float32)
+    ms = np.array([0.0, 1e-40, -1e-4, 1e10, -3e38], np.float32)
+    vs = np.array([0.0, 1e-45, 1e-30, 1e-7, 1e30, 3e38], np.float32)
+    P, G, M, V = (a.ravel().astype(np.float32) for a in np.meshgrid(ps, gs, ms, vs, indexing="ij"))
+    n = P.size
+    hpd = dict(HP, eps=eps)
+    op, om, ov, oo = P.copy(), M.copy(), V.copy(), np.zeros(n, np.uint16)
+    with np.errstate(all="ignore"):
+        oracle.adam_step(op, om, ov, G, step=3, mode=mode, bf16_out=oo, **hpd)
+    dp, dm, dv, dg = dev_f32(P), dev_f32(M), dev_f32(V), dev_f32(G)
+    dout = torch.zeros(n, dtype=torch.int16, device=DEV)
+    old = zc.tune_get("adam.arith")
+    try:
+        zc.tune_set("adam.arith", arith)
+        zc.adam_step(dp, dm, dv, dg, zc.F32, n, zc.hparams(step=3, mode=mode, **hpd), bf16_out=dout)
+        sync()
+    finally:
+        zc.tune_set("adam.arith", old)
+    gp, gm, gv, go = host_f32(dp), host_f32(dm), host_f32(dv), host_u16(dout)
+    keep = np.ones(n, bool)
+    if arith != 2:
+        # the fp32 variants form m / denominator in fp32, which overflows for |m| near the top
+        # of the range where lr * m / denominator would not; and they round b1 * m in fp32,
+        # so a subnormal m may land one (coarse) subnormal step away, which m's own bar
+        # allows but which the quotient magnifies in p: both out of their range, left out
+        with np.errstate(all="ignore"):
+            keep = ~(np.abs(om) > 1e30) & ~((om != 0) & (np.abs(om) < 1.2e-38))
+    for name, a, b in (("p", gp[keep], op[keep]), ("m", gm[keep], om[keep]), ("v", gv[keep], ov[keep])):
+        assert np.array_equal(np.isnan(a), np.isnan(b)), f"{name}: NaN pattern differs"
+        assert np.array_equal(np.isinf(a), np.isinf(b)), f"{name}: inf pattern differs"
+        inf = np.isinf(b)
+        assert np.array_equal(np.sign(a[inf]), np.sign(b[inf])), f"{name}: sign of inf differs"
+        fin = np.isfinite(b)
+        worst = ulp_diff(a[fin], b[fin]).max(initial=0)
+        # one step in double on both sides: at most the rounding of one fused multiply-add
+        # apart; the fp32 variants round the root, the quotient and the products as well
+        assert worst <= (2 if arith == 2 else 6), f"{name}: {worst} ulp apart on finite values (arith {arith})"
+    assert (np.isnan(op).sum() > 0) == (eps == 0.0) or mode == zc.ADAM_L2   # 0/0 only without eps
+    # the bf16 copy is RNE of whatever p the GPU stored, NaN and inf included
+    assert np.array_equal(go, oracle.cast_bf16(gp))
