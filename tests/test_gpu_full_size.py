@@ -190,3 +190,30 @@ def test_mixtral_unshard_per_tensor_partition_full_size():
     plan.destroy()
     del outs, gathered
     torch.cuda.empty_cache()
+
+
+def test_single_segment_longer_than_2_to_32_elements():
+    """One tensor of 2^32 + 4099 elements, source and destination both off the 16-byte grid:
+    tile indices inside one segment pass 2^24 and element indices 2^32."""
+    k = (1 << 32) + 4099
+    src_off, dst_off = 3, 1
+    gathered = torch.empty(k + src_off + 5, dtype=torch.int16, device=DEV)
+    synth.device_index_hash16_(gathered)
+    dst_full = torch.full((k + dst_off + 8,), 0x6B6B, dtype=torch.int16, device=DEV)
+    dst = dst_full[dst_off:dst_off + k]
+    plan = zc.unshard_plan_create([(src_off, dst, k)], gathered.numel())
+    zc.unshard(plan, gathered)
+    sync()
+    chunk = 1 << 28
+    for s in range(0, k, chunk):
+        e = min(k, s + chunk)
+        assert torch.equal(dst[s:e], synth.device_index_hash16_values(src_off + s, e - s, DEV)), f"chunk@{s}"
+    assert (dst_full[:dst_off] == 0x6B6B).all() and (dst_full[dst_off + k:] == 0x6B6B).all()
+    # ends and the 2^32 crossing against the oracle's element-by-element copy
+    for s in (0, (1 << 32) - 2048, k - 4096):
+        w = 4096
+        want = oracle.unshard(host_u16(gathered[src_off + s:src_off + s + w]), [0], [w])[0]
+        assert np.array_equal(host_u16(dst[s:s + w]), want)
+    plan.destroy()
+    del gathered, dst_full
+    torch.cuda.empty_cache()
