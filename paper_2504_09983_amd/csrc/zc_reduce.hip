@@ -1,7 +1,8 @@
 // Squared gradient norm and non-finite check over a flat partition.
 //
 // Streaming read (2 or 4 bytes per element).  Each lane keeps four fp32
-// partial sums (one per vector slot), a wave folds them with cross-lane
+// partial sums per tile (one per vector slot, 4-8 terms each) and folds them into a
+// double once per tile, a wave folds the lanes' doubles with cross-lane
 // shuffles (DPP / permute on gfx950), waves meet in LDS, every workgroup writes
 // one double partial, and a single small workgroup folds the partials in a
 // fixed order, so the result is deterministic for a given n.
@@ -68,12 +69,15 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
 {
     const int64_t nvec = n >> 3;
     const u32x4 *g4 = reinterpret_cast<const u32x4 *>(g);
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    double sum = 0.0;
     uint32_t worst = 0;  // running max of |bits| per half-word; >= 0x7F80 means Inf/NaN
     const int64_t tile_vecs = 256 * kReduceUnroll;
     const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t first = tile * tile_vecs + threadIdx.x;
+        // fp32 sums only within one tile (8 terms each), folded into the lane's double sum
+        // once per tile: the result stays within an fp32 rounding of the exact sum.
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         u32x4 w[kReduceUnroll];
 #pragma unroll
         for (int u = 0; u < kReduceUnroll; ++u) {
@@ -101,8 +105,8 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
             a2 = fmaf(lo[3], lo[3], a2);
             a3 = fmaf(hi[3], hi[3], a3);
         }
+        sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     }
-    double sum = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     // The last n % 8 elements, one lane each, in workgroup 0.
     const int64_t t = (nvec << 3) + threadIdx.x;
     if (blockIdx.x == 0 && threadIdx.x < 8 && t < n) {
@@ -120,12 +124,13 @@ __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict
 {
     const int64_t nvec = n >> 2;
     const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    double sum = 0.0;
     uint32_t worst = 0;
     const int64_t tile_vecs = 256 * kReduceUnroll;
     const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t first = tile * tile_vecs + threadIdx.x;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;   // 4 terms each, then into the double sum
         f32x4 x[kReduceUnroll];
 #pragma unroll
         for (int u = 0; u < kReduceUnroll; ++u) {
@@ -143,8 +148,8 @@ __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict
                             max(__float_as_uint(x[u].z) & 0x7FFFFFFFu,
                                 __float_as_uint(x[u].w) & 0x7FFFFFFFu)));
         }
+        sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     }
-    double sum = ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     const int64_t t = (nvec << 2) + threadIdx.x;
     if (blockIdx.x == 0 && threadIdx.x < 4 && t < n) {
         const float x = g[t];

@@ -359,12 +359,13 @@ def test_groups_and_device_side_clipping():
         zc.adam_step_groups(dp, dm, dv, dg, zc.BF16, n, zc.hparams(step=t, **hpd), ranges=ranges,
                             bf16_out=dout, skip_flag=flag, grad_scale_dev=scale)
         sync()
-        # the oracle takes the norm the GPU reduced (fp32) so that both clip from the same number
-        sq = np.float32(norm.item())
+        # the oracle runs its own chain (norm in double -> fp32 -> coefficient); the GPU's norm
+        # must land within an fp32 ulp of it and the coefficient within two
         want_sq, bad = oracle.grad_sqnorm(g)
-        assert bad == 0 and abs(float(sq) - want_sq) <= 1e-6 * want_sq
-        c = oracle.clip_scale(sq, 0.05, 1.0 / loss_scale)
-        assert np.float32(scale.item()) == c and float(c) < 1.0 / loss_scale      # it did clip
+        want32 = np.float32(want_sq)
+        assert bad == 0 and ulp_diff(np.float32(norm.item()), want32) <= 1
+        c = oracle.clip_scale(want32, 0.05, 1.0 / loss_scale)
+        assert ulp_diff(np.float32(scale.item()), c) <= 2 and float(c) < 1.0 / loss_scale   # it did clip
         oracle.adam_step_groups(p, m, v, g, ranges=ranges, step=t, grad_scale_dev=c, bf16_out=out, **hpd)
     check((host_f32(dp), host_f32(dm), host_f32(dv), host_u16(dout)), (p, m, v, out), tag="groups",
           steps=3, m_floor=1e-5)
@@ -386,6 +387,22 @@ def test_groups_and_device_side_clipping():
     sync()
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+def test_clip_scale_kernel_is_the_oracle_formula_bit_for_bit():
+    """Host-chosen squared norms in, coefficient out: the one-lane kernel against the oracle."""
+    cases = [(0.0, 1.0, 1.0), (1e-12, 1.0, 1.0), (4.0, 1.0, 1.0), (4.0, 0.0, 1.0), (1e6, 0.05, 1.0 / 1024),
+             (3.7e9, 1.0, 1.0 / 65536), (1e-3, 2.0, 0.5), (float(np.float32(3.3e38)), 1.0, 1.0),
+             (float("inf"), 1.0, 1.0 / 128), (2.25, 1.5, 1.0), (2.2500002, 1.5, 1.0)]
+    sq_dev = torch.zeros(1, dtype=torch.float32, device=DEV)
+    out = torch.zeros(1, dtype=torch.float32, device=DEV)
+    for sq, max_norm, inv in cases:
+        sq_dev.fill_(sq)
+        zc.clip_scale(sq_dev, max_norm, inv, out)
+        sync()
+        want = oracle.clip_scale(np.float32(sq), max_norm, inv)
+        got = np.float32(out.item())
+        assert got.view(np.uint32) == want.view(np.uint32), (sq, max_norm, inv, got, want)
 
 
 def test_whole_step_replays_from_a_hip_graph():

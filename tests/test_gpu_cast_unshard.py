@@ -205,7 +205,8 @@ def test_grad_sqnorm(n, bf16):
     sync()
     want, bad = oracle.grad_sqnorm(g)
     assert flag.item() == bad == 0
-    assert abs(out.item() - want) <= 1e-6 * want + 1e-30
+    # fp32 sums of at most 8 terms folded in double: within an fp32 ulp of the rounded exact sum
+    assert abs(out.item() - want) <= 1.3e-7 * want + 1e-30
     # deterministic
     out2 = torch.zeros_like(out)
     zc.grad_sqnorm(dg, zc.BF16 if bf16 else zc.F32, n, out2, flag)
@@ -242,7 +243,7 @@ def test_grad_sqnorm_misaligned_and_large_values():
     zc.grad_sqnorm(dg[1:], zc.F32, 5000, out, flag)
     sync()
     want, _ = oracle.grad_sqnorm(g[1:])
-    assert abs(out.item() - want) <= 1e-6 * want and flag.item() == 0
+    assert abs(out.item() - want) <= 1.3e-7 * want and flag.item() == 0
     # large finite bf16 values: flag stays 0 although the squares overflow fp32
     big = oracle.cast_bf16(np.full(64, 3e38, np.float32))
     zc.grad_sqnorm(dev_u16(big), zc.BF16, 64, out, flag)
@@ -326,4 +327,4 @@ def test_grad_accumulate_misaligned_then_feeds_the_step():
     zc.grad_sqnorm(dacc, zc.F32, n, out, flag)
     sync()
     want, bad = oracle.grad_sqnorm(a)
-    assert bad == 0 and flag.item() == 0 and abs(out.item() - want) <= 1e-6 * want
+    assert bad == 0 and flag.item() == 0 and abs(out.item() - want) <= 1.3e-7 * want
