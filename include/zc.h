@@ -376,7 +376,9 @@ zc_status zc_grad_accumulate(float *acc, const void *micro, zc_dtype micro_dtype
  * in the paper, which only states that fp32 gradients are kept).
  * g DEVICE fp32[n] or bf16[n]; sqnorm_out DEVICE float; found_inf_out DEVICE
  * int32, set to 1 when any element is NaN/Inf else 0.  Deterministic for a
- * given n (fixed reduction tree).  n == 0 writes 0 and 0.
+ * given n (fixed reduction tree); fp32 arithmetic only within groups of at most
+ * 8 squares, double from there on, so *sqnorm_out lies within one fp32 ulp of the
+ * exactly rounded sum.  n == 0 writes 0 and 0.
  * The per-workgroup partial sums live in a 64 KiB device workspace that the
  * library allocates once per device on first use and keeps; calls on one device
  * share it, so calls that overlap on different streams of one GPU race.
