@@ -207,3 +207,50 @@ def test_ring_slots_poisoned_after_use_change_nothing(transport, nbuf):
     finally:
         for k, val in old.items():
             zc.tune_set(k, val)
+
+
+def test_zero_copy_offloaded_step_replays_from_a_hip_graph():
+    """The default transport is one kernel launch over pinned host arrays: it can be captured
+    (no copy, no event wait on the host, no allocation) and every replay advances the host-resident
+    state exactly as an eager call does."""
+    n, n_res = (1 << 18) + 77, 8192
+    p0, m0, v0 = synth.host_params(n, 81), synth.host_normal(n, 1e-4, 82), np.abs(synth.host_normal(n, 1e-7, 83))
+    dg = dev_u16(oracle.cast_bf16(synth.host_grads_f32(n, 5)))
+    hp = zc.hparams(step=4, **HP)
+
+    def make():
+        return ([dev_f32(p0[:n_res]), dev_f32(m0[:n_res]), dev_f32(v0[:n_res])],
+                [pinned(p0[n_res:]), pinned(m0[n_res:]), pinned(v0[n_res:])],
+                torch.zeros(n, dtype=torch.int16, device=DEV))
+
+    ctx = zc.offload_create(1 << 18, 2)
+    assert zc.tune_get("offload.zero_copy") == 1
+    try:
+        dev_a, host_a, out_a = make()          # driven by the graph
+        dev_b, host_b, out_b = make()          # driven by eager calls
+
+        def step(dev, host, out):
+            ctx.adam_step(*dev, n_res, *host, n - n_res, dg, zc.BF16, hp, bf16_out_dev=out)
+
+        warm = make()
+        step(*warm)
+        sync()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step(dev_a, host_a, out_a)
+        sync()
+        for replay in range(3):
+            graph.replay()
+            step(dev_b, host_b, out_b)
+            sync()
+            for x, y in zip(dev_a + [out_a], dev_b + [out_b]):
+                assert torch.equal(x, y), f"replay {replay}"
+            for x, y in zip(host_a, host_b):
+                assert np.array_equal(x.numpy().view(np.uint32), y.numpy().view(np.uint32)), f"replay {replay}"
+            _ = (dev_a[0] * 2).sum().item()    # unrelated eager work and a sync between replays
+        assert not np.array_equal(host_a[0].numpy(), p0[n_res:])       # the state did move
+    finally:
+        ctx.destroy()
