@@ -271,6 +271,35 @@ def main():
     if do_step:
         result["adam_step_gparams_per_s"] = round(n / (t_adam * 1e-3) / 1e9, 2)
 
+    # ---- the update kernel's other variants on the same shard (not part of `value`) -----
+    if do_step and not args.no_next_rows:
+        def variant(fn):
+            return time_launches(torch, fn, reps=10)
+
+        def hp_next():
+            step_no[0] += 1
+            return zc.hparams(step=step_no[0], **hp_kw)
+
+        scratch = send
+        g32 = torch.empty(n, dtype=torch.float32, device=dev)
+        synth.device_normal_(g32, synth.G_STD, seed=2999)
+        rows = {
+            "bf16_grads_no_copy": (26, lambda: zc.adam_step(p, m, v, g, zc.BF16, n, hp_next())),
+            "fp32_grads_fused_copy": (30, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next(), bf16_out=scratch)),
+            "fp32_grads_no_copy": (28, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next())),
+            "unfused_step_then_cast": (32, lambda: (zc.adam_step(p, m, v, g, zc.BF16, n, hp_next()),
+                                                    zc.cast_bf16(p, scratch, n))),
+            "standalone_cast": (6, lambda: zc.cast_bf16(p, scratch, n)),
+        }
+        result["step_variants"] = {}
+        for name, (bpe, fn) in rows.items():
+            ms = variant(fn)
+            result["step_variants"][name] = {"bytes_per_element": bpe, "ms": round(ms, 4),
+                                             "GBps": round(gb(bpe * n) / (ms * 1e-3), 1),
+                                             "frac": round(gb(bpe * n) / (ms * 1e-3) / HBM_PEAK_GBS, 4),
+                                             "gparams_per_s": round(n / (ms * 1e-3) / 1e9, 2)}
+        del g32
+
     # ---- free the resident workload before the extra legs --------------------------
     if do_unshard:
         plan.destroy()
