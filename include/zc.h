@@ -409,6 +409,8 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
  *                      more than num_buffers chunks ahead of finished copy-backs (deep copy
  *                      queues were measured to halve the link rate); 0 = enqueue everything
  *   "offload.d2h_on_compute" 1 = the staged ring copies back on `hip_stream`
+ *   "offload.overlap_resident" 1 (default) = in the zero-copy transport the resident prefix runs on
+ *                      an internal stream beside the link-bound launch, joined before the call returns
  *   "offload.poison"   1 = every ring slot is overwritten with 0xDEADBEEF once its chunk has
  *                      left it (a test aid: a missing fence then shows up as garbage)
  */

@@ -141,6 +141,7 @@ static const Knob kKnobs[] = {
     {"offload.max_ahead", &Tune::offload_max_ahead, 0, 1},
     {"offload.d2h_on_compute", &Tune::offload_d2h_on_compute, 0, 1},
     {"offload.poison", &Tune::offload_poison, 0, 1},
+    {"offload.overlap_resident", &Tune::offload_overlap_resident, 0, 1},
 };
 
 static const Knob *find_knob(const char *key)

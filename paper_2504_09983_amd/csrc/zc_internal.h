@@ -42,6 +42,7 @@ struct Tune {
     int64_t offload_zc_waves_per_cu = 0;
     int64_t offload_max_ahead = 1;
     int64_t offload_d2h_on_compute = 0;
+    int64_t offload_overlap_resident = 1;   // zero-copy: resident prefix on a side stream
     int64_t offload_poison = 0;      // overwrite every ring slot once its chunk has left it
 };
 Tune &tune();

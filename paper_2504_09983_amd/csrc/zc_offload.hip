@@ -293,17 +293,10 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
 
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    // Resident prefix: one ordinary launch on the caller's stream.
-    if (n_resident > 0)
-        ZC_TRY(launch_adam(p_dev, m_dev, v_dev, g_dev, g_dtype, n_resident, hp, bf16_out_dev, skip_flag,
-                           stream));
-    if (n_streamed == 0)
-        return ZC_OK;
-
     const char *g_tail = static_cast<const char *>(g_dev) + n_resident * g_size;
     uint16_t *out_tail = bf16_out_dev ? bf16_out_dev + n_resident : nullptr;
 
-    if (tune().offload_zero_copy == 1) {
+    if (tune().offload_zero_copy == 1 && n_streamed > 0) {
         // The update kernel itself reads and writes the pinned host arrays through the
         // link: no staging, no copy engines, one launch.  The link is the bound, so the
         // HBM-motivated cap on resident waves is lifted (more requests in flight).
@@ -311,9 +304,34 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
         ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&pd), p_host, 0));
         ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&md), m_host, 0));
         ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&vd), v_host, 0));
-        return launch_adam(pd, md, vd, g_tail, g_dtype, n_streamed, hp, out_tail, skip_flag, stream,
-                           (int)tune().offload_zc_waves_per_cu);
+        const bool side = n_resident > 0 && tune().offload_overlap_resident != 0;
+        if (side) {
+            // The resident prefix is bound by HBM, the streamed suffix by the link: run the
+            // prefix on an internal stream next to the long link-bound launch instead of in
+            // front of it (fork after what the caller has enqueued, join before returning).
+            ZC_HIP(hipEventRecord(ctx->entry, stream));
+            ZC_HIP(hipStreamWaitEvent(ctx->h2d, ctx->entry, 0));
+        }
+        // Prefix first: its short-lived workgroups take the compute units at once and hand
+        // them over to the link-bound launch as they retire.
+        if (n_resident > 0)
+            ZC_TRY(launch_adam(p_dev, m_dev, v_dev, g_dev, g_dtype, n_resident, hp, bf16_out_dev, skip_flag,
+                               side ? ctx->h2d : stream));
+        ZC_TRY(launch_adam(pd, md, vd, g_tail, g_dtype, n_streamed, hp, out_tail, skip_flag, stream,
+                           (int)tune().offload_zc_waves_per_cu));
+        if (side) {
+            ZC_HIP(hipEventRecord(ctx->done, ctx->h2d));
+            ZC_HIP(hipStreamWaitEvent(stream, ctx->done, 0));
+        }
+        return ZC_OK;
     }
+
+    // Resident prefix: one ordinary launch on the caller's stream.
+    if (n_resident > 0)
+        ZC_TRY(launch_adam(p_dev, m_dev, v_dev, g_dev, g_dtype, n_resident, hp, bf16_out_dev, skip_flag,
+                           stream));
+    if (n_streamed == 0)
+        return ZC_OK;
 
     // Fence the copy streams behind whatever the caller has already enqueued.
     ZC_HIP(hipEventRecord(ctx->entry, stream));
