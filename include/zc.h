@@ -214,7 +214,9 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  * concatenation either way):
  *   1 (default)  the update kernel reads and writes the pinned host arrays
  *                directly through the link; one launch on `hip_stream`, no
- *                staging memory, no copy engines.
+ *                staging memory, no copy engines.  A resident prefix is updated
+ *                by a second launch on an internal stream that forks from and
+ *                rejoins `hip_stream` inside the call.
  *   0            staged ring: host -> staging slot -> kernel -> host in chunks
  *                of chunk_bytes per array through num_buffers slots, copies on
  *                two internal streams (hipMemcpyAsync) and the kernel on
