@@ -52,6 +52,9 @@ def parse_args():
                          "(same resident fraction) when its streamed part would need more")
     ap.add_argument("--offload-chunk-mib", type=int, default=64)
     ap.add_argument("--offload-buffers", type=int, default=3)
+    ap.add_argument("--offload-transports", default="1,2,0",
+                    help="which transports the offload leg times: 1 zero-copy, 2 staged reads + direct "
+                         "writes, 0 staged ring")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true",
                     help="skip the short legs for gradient accumulation and the per-tensor layout")
@@ -315,7 +318,9 @@ def main():
     if args.offload_elems > 0:
         legs = {}
         keep = zc.tune_get("offload.zero_copy")
-        for mode, name in ((1, "zero_copy"), (2, "staged_reads_direct_writes"), (0, "staged_ring")):
+        names = {1: "zero_copy", 2: "staged_reads_direct_writes", 0: "staged_ring"}
+        for mode in (int(x) for x in args.offload_transports.split(",")):
+            name = names[mode]
             zc.tune_set("offload.zero_copy", mode)
             legs[name] = offload_leg(torch, synth, zc, dev, args, probe=(mode == 0))
         zc.tune_set("offload.zero_copy", keep)
