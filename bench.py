@@ -513,7 +513,30 @@ def cpu_baseline_leg(synth):
         oracle.adam_step(p, m, v, g, step=t, bf16_out=send, skip=bool(bad), **synth.HP)
         oracle.unshard(gathered, offs, nums)
     dt = (time.perf_counter() - t0) / passes
+
+    # The same oracle calls on disjoint slices from a pool of threads (the C functions run
+    # without the interpreter lock): what all the host's cores reach together.
+    from concurrent.futures import ThreadPoolExecutor
+    threads = max(1, min(16, os.cpu_count() or 1))
+    bounds = [ns * k // threads for k in range(threads + 1)]
+    gb_ = [WORLD * ns * k // threads for k in range(threads + 1)]
+
+    def work(k, t):
+        a, b = bounds[k], bounds[k + 1]
+        _, bad = oracle.grad_sqnorm(g[a:b])
+        oracle.adam_step(p[a:b], m[a:b], v[a:b], g[a:b], step=t, bf16_out=send[a:b], skip=bool(bad), **synth.HP)
+        oracle.unshard(gathered[gb_[k]:gb_[k + 1]], [0], [gb_[k + 1] - gb_[k]])
+
+    par_passes = 4
+    with ThreadPoolExecutor(threads) as pool:
+        list(pool.map(lambda k: work(k, passes + 1), range(threads)))       # warm the pool
+        t1 = time.perf_counter()
+        for t in range(par_passes):
+            list(pool.map(lambda k: work(k, passes + 2 + t), range(threads)))
+        dt_par = (time.perf_counter() - t1) / par_passes
     return {"value": round(ns / dt / 1e9, 4), "unit": "Gparams/s", "cores": 1, "kind": "oracle",
+            "all_cores": {"value": round(ns / dt_par / 1e9, 4), "unit": "Gparams/s", "cores": threads,
+                          "sample": f"{par_passes} passes, the same calls on {threads} disjoint slices in {threads} threads"},
             "sample": (f"{passes} passes over a 2^26-element shard slice (grad-norm + AdamW + bf16 "
                        f"copy) and its 8 x 2^26-element gathered buffer (unshard); "
                        f"{round(dt, 2)} s per pass; host has {os.cpu_count()} logical CPUs, "
