@@ -3,8 +3,8 @@
  *
  * C ABI.  Plain pointers and sizes only.  Every pointer is marked HOST or
  * DEVICE below.  The caller owns every data buffer; the library owns only what
- * a *_create call returns and the small per-device reduction workspace it
- * allocates on first use of zc_grad_sqnorm.
+ * a *_create call returns and the small reduction workspaces (64 KiB per device
+ * and stream) it allocates on first use of zc_grad_sqnorm.
  *
  * Stream semantics: every call that takes `hip_stream` (a hipStream_t passed
  * as void*, NULL = the null stream) only enqueues work on it and returns; no
@@ -382,8 +382,10 @@ zc_status zc_grad_accumulate(float *acc, const void *micro, zc_dtype micro_dtype
  * 8 squares, double from there on, so *sqnorm_out lies within one fp32 ulp of the
  * exactly rounded sum.  n == 0 writes 0 and 0.
  * The per-workgroup partial sums live in a 64 KiB device workspace that the
- * library allocates once per device on first use and keeps; calls on one device
- * share it, so calls that overlap on different streams of one GPU race.
+ * library allocates on the first call on a (device, stream) pair and keeps, so
+ * calls on different streams do not interfere.  That first call must happen
+ * outside a graph capture (inside one it returns ZC_ERR_UNSUPPORTED and enqueues
+ * nothing).
  */
 zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
                          int32_t *found_inf_out, void *hip_stream);

@@ -6,7 +6,10 @@
 // shuffles (DPP / permute on gfx950), waves meet in LDS, every workgroup writes
 // one double partial, and a single small workgroup folds the partials in a
 // fixed order, so the result is deterministic for a given n.
+#include <map>
 #include <mutex>
+#include <new>
+#include <utility>
 
 #include "zc_internal.h"
 
@@ -200,24 +203,40 @@ __global__ __launch_bounds__(256) void sqnorm_final_kernel(const Partial *__rest
     }
 }
 
-// Per-device workspace for the partials, allocated on first use and kept.
-static zc_status partials_buffer(Partial **out)
+// Workspace for the partials: one 64 KiB buffer per (device, stream), allocated on the first
+// call that names that pair and kept until the process ends, so that calls enqueued on
+// different streams never share partial sums.  A stream handle that is destroyed and handed
+// out again simply finds its predecessor's buffer.
+static zc_status partials_buffer(hipStream_t stream, Partial **out)
 {
     static std::mutex mu;
-    static Partial *bufs[64];
+    static std::map<std::pair<int, hipStream_t>, Partial *> bufs;
     int dev = 0;
     ZC_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= 64)
-        return fail(ZC_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
     std::lock_guard<std::mutex> lock(mu);
-    if (!bufs[dev]) {
-        hipError_t e = hipMalloc(reinterpret_cast<void **>(&bufs[dev]), sizeof(Partial) * kMaxPartials);
-        if (e != hipSuccess) {
-            bufs[dev] = nullptr;
+    const auto key = std::make_pair(dev, stream);
+    auto it = bufs.find(key);
+    if (it == bufs.end()) {
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &capturing) != hipSuccess)
+            (void)hipGetLastError();
+        if (capturing != hipStreamCaptureStatusNone)
+            return fail(ZC_ERR_UNSUPPORTED, "the first zc_grad_sqnorm on a stream allocates its workspace: "
+                                            "call it once on this stream before capturing");
+        if (bufs.size() >= 1024)
+            return fail(ZC_ERR_NOMEM, "more than 1024 (device, stream) pairs have called zc_grad_sqnorm");
+        Partial *buf = nullptr;
+        hipError_t e = hipMalloc(reinterpret_cast<void **>(&buf), sizeof(Partial) * kMaxPartials);
+        if (e != hipSuccess)
             return hip_fail(e, "hipMalloc(reduction workspace)");
+        try {
+            it = bufs.emplace(key, buf).first;
+        } catch (const std::bad_alloc &) {
+            (void)hipFree(buf);
+            return fail(ZC_ERR_NOMEM, "cannot record the reduction workspace");
         }
     }
-    *out = bufs[dev];
+    *out = it->second;
     return ZC_OK;
 }
 
@@ -244,7 +263,7 @@ extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, 
 
     hipStream_t stream = (hipStream_t)hip_stream;
     Partial *partials = nullptr;
-    ZC_TRY(partials_buffer(&partials));
+    ZC_TRY(partials_buffer(stream, &partials));
     int cus = 0;
     ZC_TRY(num_cus(&cus));
 

@@ -432,13 +432,17 @@ def test_whole_step_replays_from_a_hip_graph():
         zc.adam_step(*st, dg, zc.BF16, n, hp, bf16_out=snd, skip_flag=flag)
         zc.unshard(plan, snd)
 
-    warm = [x.clone() for x in state]
-    step(warm, torch.zeros_like(send))            # warms the library's lazily created workspace
-    sync()
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
+        with pytest.raises(zc.ZcError) as err:     # a first call on this stream inside a capture is refused
+            with torch.cuda.graph(torch.cuda.CUDAGraph(), stream=side):
+                zc.grad_sqnorm(dg, zc.BF16, n, norm, flag)
+        assert err.value.status == zc.ERR_UNSUPPORTED
+        warm = [x.clone() for x in state]
+        step(warm, torch.zeros_like(send))        # creates this stream's reduction workspace
+        side.synchronize()
         with torch.cuda.graph(graph, stream=side):
             step(state, send)
     sync()

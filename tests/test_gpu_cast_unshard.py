@@ -328,3 +328,26 @@ def test_grad_accumulate_misaligned_then_feeds_the_step():
     sync()
     want, bad = oracle.grad_sqnorm(a)
     assert bad == 0 and flag.item() == 0 and abs(out.item() - want) <= 1.3e-7 * want
+
+
+def test_grad_sqnorm_on_two_streams_at_once():
+    """Each stream has its own partial sums: interleaved launches on two streams over different
+    gradients give each its own norm, every time."""
+    n = (1 << 22) + 11
+    ga = synth.host_grads_f32(n, 61)
+    gb = (synth.host_grads_f32(n, 62) * np.float32(3.0)).astype(np.float32)
+    da, db = dev_f32(ga), dev_f32(gb)
+    want_a, want_b = oracle.grad_sqnorm(ga)[0], oracle.grad_sqnorm(gb)[0]
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs_a = torch.zeros(32, dtype=torch.float32, device=DEV)
+    outs_b = torch.zeros(32, dtype=torch.float32, device=DEV)
+    flags = torch.zeros(64, dtype=torch.int32, device=DEV)
+    sync()
+    for i in range(32):
+        zc.grad_sqnorm(da, zc.F32, n, outs_a[i:i + 1], flags[i:i + 1], stream=sa)
+        zc.grad_sqnorm(db, zc.F32, n, outs_b[i:i + 1], flags[32 + i:33 + i], stream=sb)
+    sync()
+    assert not flags.any()
+    assert np.all(np.abs(outs_a.cpu().numpy() - want_a) <= 1.3e-7 * want_a)
+    assert np.all(np.abs(outs_b.cpu().numpy() - want_b) <= 1.3e-7 * want_b)
+    assert len(set(outs_a.cpu().numpy().tolist())) == 1 and len(set(outs_b.cpu().numpy().tolist())) == 1
