@@ -95,9 +95,6 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
             for (int k = 0; k < 4; ++k) {
                 lo[k] = __uint_as_float(ws[k] << 16);
                 hi[k] = __uint_as_float(ws[k] & 0xFFFF0000u);
-                const uint32_t mag_lo = ws[k] & 0x7FFFu;
-                const uint32_t mag_hi = (ws[k] >> 16) & 0x7FFFu;
-                worst = max(worst, max(mag_lo, mag_hi));
             }
             a0 = fmaf(lo[0], lo[0], a0);
             a1 = fmaf(hi[0], hi[0], a1);
@@ -107,6 +104,19 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
             a1 = fmaf(hi[2], hi[2], a1);
             a2 = fmaf(lo[3], lo[3], a2);
             a3 = fmaf(hi[3], hi[3], a3);
+        }
+        const float tile_sum = (a0 + a1) + (a2 + a3);
+        // A NaN or Inf element makes its tile's fp32 sum non-finite; so does the square of a
+        // finite value above 1.8e19, which must not raise the flag.  Only such a tile looks
+        // at its elements one by one (they are still in registers).
+        if (!(fabsf(tile_sum) <= 3.4028234e38f)) {
+#pragma unroll
+            for (int u = 0; u < kReduceUnroll; ++u) {
+                const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    worst = max(worst, max(ws[k] & 0x7FFFu, (ws[k] >> 16) & 0x7FFFu));
+            }
         }
         sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     }
@@ -146,10 +156,15 @@ __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict
             a1 = fmaf(x[u].y, x[u].y, a1);
             a2 = fmaf(x[u].z, x[u].z, a2);
             a3 = fmaf(x[u].w, x[u].w, a3);
-            worst = max(max(worst, __float_as_uint(x[u].x) & 0x7FFFFFFFu),
-                        max(__float_as_uint(x[u].y) & 0x7FFFFFFFu,
-                            max(__float_as_uint(x[u].z) & 0x7FFFFFFFu,
-                                __float_as_uint(x[u].w) & 0x7FFFFFFFu)));
+        }
+        const float tile_sum = (a0 + a1) + (a2 + a3);
+        if (!(fabsf(tile_sum) <= 3.4028234e38f)) {   // see the bf16 kernel: only then look closer
+#pragma unroll
+            for (int u = 0; u < kReduceUnroll; ++u)
+                worst = max(max(worst, __float_as_uint(x[u].x) & 0x7FFFFFFFu),
+                            max(__float_as_uint(x[u].y) & 0x7FFFFFFFu,
+                                max(__float_as_uint(x[u].z) & 0x7FFFFFFFu,
+                                    __float_as_uint(x[u].w) & 0x7FFFFFFFu)));
         }
         sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     }
