@@ -534,6 +534,9 @@ extern "C" zc_status zc_adam_step_groups(float *p, float *m, float *v, const voi
         if (!(k.lr_scale == k.lr_scale) || k.lr_scale - k.lr_scale != 0.0f ||
             !(k.weight_decay == k.weight_decay) || k.weight_decay - k.weight_decay != 0.0f)
             return fail(ZC_ERR_INVALID_ARG, "range %lld: lr_scale and weight_decay must be finite", (long long)r);
+        const float lr_here = hp->lr * k.lr_scale;
+        if (lr_here - lr_here != 0.0f)
+            return fail(ZC_ERR_INVALID_ARG, "range %lld: lr * lr_scale is not finite", (long long)r);
         prev_end = k.end;
     }
     if (n == 0)
