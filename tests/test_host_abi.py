@@ -82,7 +82,8 @@ def test_adam_step_rejects_bad_arguments_without_a_gpu():
     for bad in ([(4, 2, 1.0, 0.0)], [(0, 9, 1.0, 0.0)], [(0, 4, 1.0, 0.0), (3, 6, 1.0, 0.0)],
                 [(0, 4, float("nan"), 0.0)], [(-1, 4, 1.0, 0.0)]):
         assert _status(zc.adam_step_groups, *ok, ranges=bad, stream=0) == zc.ERR_INVALID_ARG
-    assert _status(zc.adam_step_groups, *ok, ranges=[(0, 4, 3e38, 0.0)], stream=0) == zc.ERR_INVALID_ARG   # lr * scale overflows
+    big_lr = (A, A + 64, A + 128, A + 192, zc.F32, 8, zc.hparams(step=1, **dict(HP, lr=1e10)))
+    assert _status(zc.adam_step_groups, *big_lr, ranges=[(0, 4, 3e38, 0.0)], stream=0) == zc.ERR_INVALID_ARG   # lr * scale overflows
     assert _status(zc.adam_step_groups, *ok, grad_scale_dev=A + 1, stream=0) == zc.ERR_ALIGNMENT
     assert _status(zc.clip_scale, 0, 1.0, 1.0, A, stream=0) == zc.ERR_INVALID_ARG
     assert _status(zc.clip_scale, A, -1.0, 1.0, A + 4, stream=0) == zc.ERR_INVALID_ARG
