@@ -189,6 +189,8 @@ zc_status zc_flat_layout(const int64_t *numels, int64_t ntensors, int32_t world,
 {
     if (ntensors < 0 || world < 1 || shard_align < 1)
         return zc::fail(ZC_ERR_INVALID_ARG, "need ntensors >= 0, world >= 1, shard_align >= 1");
+    if (shard_align > zc::kMaxElements)
+        return zc::fail(ZC_ERR_UNSUPPORTED, "shard_align exceeds 2^40 elements");
     if (ntensors > 0 && (!numels || !offsets_out))
         return zc::fail(ZC_ERR_INVALID_ARG, "numels / offsets_out is NULL");
     if (!shard_numel_out || !total_out)
@@ -220,6 +222,8 @@ zc_status zc_per_tensor_layout(const int64_t *numels, int64_t ntensors, int32_t 
 {
     if (ntensors < 0 || world < 1 || align < 1)
         return zc::fail(ZC_ERR_INVALID_ARG, "need ntensors >= 0, world >= 1, align >= 1");
+    if (align > zc::kMaxElements)
+        return zc::fail(ZC_ERR_UNSUPPORTED, "align exceeds 2^40 elements");
     if (ntensors > 0 && (!numels || !src_offsets_out || !dst_offsets_out || !seg_numels_out))
         return zc::fail(ZC_ERR_INVALID_ARG, "numels or an output table is NULL");
     if (!send_numel_out)

@@ -33,6 +33,14 @@ static void expect_error(zc_status s)
 
 static void extreme_sizes()
 {
+    {
+        // an alignment near INT64_MAX must be refused, not rounded up to
+        std::vector<int64_t> one = {5};
+        std::vector<int64_t> o(2), a(9), b(9), c(9);
+        int64_t shard = 0, total = 0, send = 0;
+        expect_error(zc_flat_layout(one.data(), 1, 8, INT64_MAX - 3, o.data(), &shard, &total));
+        expect_error(zc_per_tensor_layout(one.data(), 1, 8, INT64_MAX - 3, a.data(), b.data(), c.data(), &send));
+    }
     int64_t big = INT64_MAX / 2;
     std::vector<int64_t> numels = {big, big, big, 7};
     std::vector<int64_t> offs(5); int64_t shard = 0, total = 0;
