@@ -290,6 +290,8 @@ zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t 
         return fail(ZC_ERR_INVALID_ARG, "segs is NULL");
     if (gathered_numel > kMaxElements * 64)
         return fail(ZC_ERR_UNSUPPORTED, "gathered buffer exceeds 2^46 elements");
+    if (nsegs > 0x7FFFFFFF)
+        return fail(ZC_ERR_UNSUPPORTED, "more than 2^31 segments");
 
     std::vector<SegDesc> table;
     try {
@@ -326,8 +328,6 @@ zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t 
         table.push_back(d);
     }
 
-    if (nsegs > 0x7FFFFFFF)
-        return fail(ZC_ERR_UNSUPPORTED, "more than 2^31 segments");
     // hint[k] = last segment whose first tile is <= k << kHintShift, for k = 0 .. groups
     const int64_t groups = (ntiles >> kHintShift) + 1;
     std::vector<int32_t> hints;
