@@ -391,6 +391,24 @@ zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqno
                          int32_t *found_inf_out, void *hip_stream);
 
 /*
+ * zc_grad_sqnorm for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels, same result bit for bit; the per-workgroup partial sums go to a fixed
+ * 64 KiB array (4096 entries of 16 bytes) inside the library's device image
+ * instead of an allocated workspace, so this call never allocates or frees
+ * memory.  The grid is capped at 4096 workgroups, which serves every n up to the
+ * library's limit of 2^40 elements; a larger n is refused with
+ * ZC_ERR_UNSUPPORTED before anything is enqueued.  Each GPU holds one copy of
+ * the array for the life of the process; its address is looked up once per
+ * device on the first call made with that device current.  The array needs no
+ * clearing (every entry read was written by the same call), but all calls on a
+ * GPU share it whatever their stream: two calls whose kernels can overlap on one
+ * GPU race and give garbage; order them on one stream or with events.
+ */
+zc_status zc_grad_sqnorm_static(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
+                                int32_t *found_inf_out, void *hip_stream);
+
+/*
  * Tuning knobs for measurement sweeps (process-wide, not thread-safe against
  * concurrent launches).  Unknown key -> ZC_ERR_INVALID_ARG.  Keys:
  *   "adam.rows"        128-bit vectors per lane per tile: 1, 2 or 4

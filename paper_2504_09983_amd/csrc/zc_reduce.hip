@@ -255,12 +255,10 @@ static zc_status partials_buffer(hipStream_t stream, Partial **out)
     return ZC_OK;
 }
 
-}  // namespace zc
-
-extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
-                                    int32_t *found_inf_out, void *hip_stream)
+// Argument checks shared by both entry points; nothing is enqueued here.
+static zc_status check_sqnorm_args(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
+                                   int32_t *found_inf_out)
 {
-    using namespace zc;
     if (n < 0)
         return fail(ZC_ERR_INVALID_ARG, "n is negative (%lld)", (long long)n);
     if (n > kMaxElements)
@@ -272,16 +270,19 @@ extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, 
         return fail(ZC_ERR_ALIGNMENT, "outputs must be 4-byte aligned");
     if (n > 0 && !g)
         return fail(ZC_ERR_INVALID_ARG, "g is NULL");
-    const bool bf16 = g_dtype == ZC_BF16;
-    if (n > 0 && !aligned_to(g, bf16 ? 2 : 4))
+    if (n > 0 && !aligned_to(g, g_dtype == ZC_BF16 ? 2 : 4))
         return fail(ZC_ERR_ALIGNMENT, "g is not aligned to its element size");
+    return ZC_OK;
+}
 
-    hipStream_t stream = (hipStream_t)hip_stream;
-    Partial *partials = nullptr;
-    ZC_TRY(partials_buffer(stream, &partials));
+// The two launches (partials, then the fixed-order fold) over a partials buffer of
+// kMaxPartials entries.  Every workgroup overwrites its own entry and the fold reads only
+// the entries written by this call, so the buffer needs no clearing between calls.
+static zc_status enqueue_sqnorm(const void *g, bool bf16, int64_t n, float *sqnorm_out,
+                                int32_t *found_inf_out, hipStream_t stream, Partial *partials)
+{
     int cus = 0;
     ZC_TRY(num_cus(&cus));
-
     int blocks = 0;
     if (n > 0) {
         const int64_t per_lane = (bf16 ? 8 : 4) * kReduceUnroll;
@@ -311,4 +312,54 @@ extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, 
                        found_inf_out);
     ZC_HIP(hipGetLastError());
     return ZC_OK;
+}
+
+// Partials buffer of zc_grad_sqnorm_static: one fixed array in the library's device image,
+// so that entry point never allocates.  Every GPU the library runs on holds its own copy at
+// its own address; host code must use the address hipGetSymbolAddress returns for the
+// current device, never the symbol itself.
+static __device__ __align__(256) unsigned char scratch[sizeof(Partial) * kMaxPartials];
+
+static zc_status static_partials(Partial **out)
+{
+    static std::mutex mu;
+    static Partial *ptr_of_device[64];
+    int dev = 0;
+    ZC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return fail(ZC_ERR_UNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {
+        void *ptr = nullptr;
+        ZC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr)
+            return fail(ZC_ERR_HIP, "hipGetSymbolAddress gave no address for the static partials buffer");
+        ptr_of_device[dev] = static_cast<Partial *>(ptr);
+    }
+    *out = ptr_of_device[dev];
+    return ZC_OK;
+}
+
+}  // namespace zc
+
+extern "C" zc_status zc_grad_sqnorm(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
+                                    int32_t *found_inf_out, void *hip_stream)
+{
+    using namespace zc;
+    ZC_TRY(check_sqnorm_args(g, g_dtype, n, sqnorm_out, found_inf_out));
+    hipStream_t stream = (hipStream_t)hip_stream;
+    Partial *partials = nullptr;
+    ZC_TRY(partials_buffer(stream, &partials));
+    return enqueue_sqnorm(g, g_dtype == ZC_BF16, n, sqnorm_out, found_inf_out, stream, partials);
+}
+
+extern "C" zc_status zc_grad_sqnorm_static(const void *g, zc_dtype g_dtype, int64_t n, float *sqnorm_out,
+                                           int32_t *found_inf_out, void *hip_stream)
+{
+    using namespace zc;
+    ZC_TRY(check_sqnorm_args(g, g_dtype, n, sqnorm_out, found_inf_out));
+    Partial *partials = nullptr;
+    ZC_TRY(static_partials(&partials));
+    return enqueue_sqnorm(g, g_dtype == ZC_BF16, n, sqnorm_out, found_inf_out, (hipStream_t)hip_stream,
+                          partials);
 }

@@ -132,6 +132,8 @@ def lib():
     L.zc_grad_accumulate.argtypes = [vp, vp, ctypes.c_int, i64, ctypes.c_float, vp]
     L.zc_grad_sqnorm.restype = ctypes.c_int
     L.zc_grad_sqnorm.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp]
+    L.zc_grad_sqnorm_static.restype = ctypes.c_int
+    L.zc_grad_sqnorm_static.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp]
     L.zc_tune_set.restype = ctypes.c_int
     L.zc_tune_set.argtypes = [ctypes.c_char_p, i64]
     L.zc_tune_get.restype = ctypes.c_int
@@ -410,6 +412,11 @@ def grad_accumulate(acc, micro, micro_dtype: int, n: int, scale: float = 1.0, st
 def grad_sqnorm(g, g_dtype: int, n: int, sqnorm_out, found_inf_out, stream=None) -> None:
     _check(lib().zc_grad_sqnorm(_addr(g), g_dtype, n, _addr(sqnorm_out), _addr(found_inf_out),
                                 _stream(stream)))
+
+
+def grad_sqnorm_static(g, g_dtype: int, n: int, sqnorm_out, found_inf_out, stream=None) -> None:
+    _check(lib().zc_grad_sqnorm_static(_addr(g), g_dtype, n, _addr(sqnorm_out), _addr(found_inf_out),
+                                       _stream(stream)))
 
 
 def tune_set(key: str, value: int) -> None:
