@@ -409,14 +409,18 @@ zc_status zc_grad_sqnorm_static(const void *g, zc_dtype g_dtype, int64_t n, floa
                                 int32_t *found_inf_out, void *hip_stream);
 
 /*
- * Tuning knobs for measurement sweeps (process-wide, not thread-safe against
- * concurrent launches).  Unknown key -> ZC_ERR_INVALID_ARG.  Keys:
- *   "adam.rows"        128-bit vectors per lane per tile: 1, 2 or 4
- *   "adam.block"       threads per workgroup: 64, 128 or 256
+ * Tuning knobs for measurement sweeps.  The knobs belong to the calling thread:
+ * zc_tune_set changes what later calls made by the same thread launch, and no
+ * other thread's; a thread that never calls it launches the defaults, whatever
+ * other threads have set.  Unknown key -> ZC_ERR_INVALID_ARG.  Keys:
+ *   "adam.rows"        128-bit vectors per lane per tile: 1 (default), 2 or 4
+ *   "adam.block"       threads per workgroup: 64 (default), 128 or 256
  *   "adam.waves_per_cu" cap on resident waves per compute unit, enforced through an
  *                      unused dynamic-LDS request; 0 = no cap; -1 (default) = 12 with
- *                      bf16 gradients and the fused bf16 copy, 10 otherwise
- *   "adam.nontemporal" 0/1 non-temporal loads and stores
+ *                      bf16 gradients, 11 with fp32 gradients, one more from 2^32
+ *                      elements on
+ *   "adam.nontemporal" 0 = ordinary loads and stores, 1 (default) = both non-temporal,
+ *                      2 = loads only, 3 = stores only
  *   "adam.arith"       0 = fp32 only, 1 = fp64 multiply-adds with fp32 sqrt/div,
  *                      2 = fp64 throughout
  *   "copy.waves_per_cu", "cast.waves_per_cu", "accum.waves_per_cu"  the same cap for

@@ -88,21 +88,43 @@ __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g,
         p = fmaf(-s.step_sizef, upd, pd);
         m = mn;
         v = vn;
-    } else {
+    } else if constexpr (ARITH == 1) {
         double gd = (double)g * s.gscale;
         if (s.l2)
             gd = fma(s.wd, (double)p, gd);
         const float mn = (float)fma(s.omb1, gd, s.b1 * (double)m);
         const float vn = (float)fma(s.omb2 * gd, gd, s.b2 * (double)v);
         const double pd = s.l2 ? (double)p : (double)p * s.decay;
-        if constexpr (ARITH == 1) {
-            const float denom = fmaf(sqrtf(vn), s.inv_sqrt_bc2f, s.epsf);
-            const float upd = mn / denom;
-            p = (float)fma(-s.step_size, (double)upd, pd);
-        } else {
-            const double denom = fma(sqrt((double)vn), s.inv_sqrt_bc2, s.eps);
-            p = (float)(pd - s.step_size * (double)mn / denom);
+        const float denom = fmaf(sqrtf(vn), s.inv_sqrt_bc2f, s.epsf);
+        const float upd = mn / denom;
+        p = (float)fma(-s.step_size, (double)upd, pd);
+        m = mn;
+        v = vn;
+    } else {
+        // The definition evaluated in IEEE double, every product and sum rounded on its
+        // own (contraction into fused multiply-adds is switched off for this block), then
+        // one rounding to fp32 per stored value:
+        //   m = b1*m + (1-b1)*g,  v = b2*v + ((1-b2)*g)*g
+        // so m and v reproduce bit for bit on any IEEE machine that evaluates the same
+        // expression in double.
+        float mn, vn;
+        {
+#pragma clang fp contract(off)
+            double gd = (double)g * s.gscale;
+            if (s.l2) {
+                const double wp = s.wd * (double)p;
+                gd = gd + wp;
+            }
+            const double m_keep = s.b1 * (double)m;
+            const double m_add = s.omb1 * gd;
+            mn = (float)(m_keep + m_add);
+            const double v_keep = s.b2 * (double)v;
+            const double v_add = (s.omb2 * gd) * gd;
+            vn = (float)(v_keep + v_add);
         }
+        const double pd = s.l2 ? (double)p : (double)p * s.decay;
+        const double denom = fma(sqrt((double)vn), s.inv_sqrt_bc2, s.eps);
+        p = (float)(pd - s.step_size * (double)mn / denom);
         m = mn;
         v = vn;
     }
@@ -135,7 +157,8 @@ __device__ __forceinline__ void st(T *ptr, T val)
         *ptr = val;
 }
 
-template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH, bool GUARD>
+// NT: 0 = ordinary loads and stores, 1 = both non-temporal, 2 = loads only, 3 = stores only.
+template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH, bool GUARD>
 __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, const f32x4 *v4,
                                           f32x4 *po4, f32x4 *mo4, f32x4 *vo4,
                                           const void *__restrict__ g, u32x2 *__restrict__ out2,
@@ -145,22 +168,23 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
     // used after the tile's loads have been issued, so their latency hides behind them.
     const int32_t skip_now = ctl.skip ? *ctl.skip : 0;
     const float dev_scale = ctl.gscale ? *ctl.gscale : 1.0f;
+    constexpr bool NTL = NT == 1 || NT == 2, NTS = NT == 1 || NT == 3;
     f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int64_t i = first + (int64_t)r * BLOCK;
         if (!GUARD || i < nvec) {
-            pv[r] = ld<NT>(p4 + i);
-            mv[r] = ld<NT>(m4 + i);
-            vv[r] = ld<NT>(v4 + i);
+            pv[r] = ld<NTL>(p4 + i);
+            mv[r] = ld<NTL>(m4 + i);
+            vv[r] = ld<NTL>(v4 + i);
             if constexpr (G_BF16) {
-                const u32x2 w = ld<NT>(reinterpret_cast<const u32x2 *>(g) + i);
+                const u32x2 w = ld<NTL>(reinterpret_cast<const u32x2 *>(g) + i);
                 gv[r].x = __uint_as_float(w.x << 16);
                 gv[r].y = __uint_as_float(w.x & 0xFFFF0000u);
                 gv[r].z = __uint_as_float(w.y << 16);
                 gv[r].w = __uint_as_float(w.y & 0xFFFF0000u);
             } else {
-                gv[r] = ld<NT>(reinterpret_cast<const f32x4 *>(g) + i);
+                gv[r] = ld<NTL>(reinterpret_cast<const f32x4 *>(g) + i);
             }
         }
     }
@@ -183,14 +207,14 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
                 mv[r][k] = me;
                 vv[r][k] = ve;
             }
-            st<NT>(po4 + i, pv[r]);
-            st<NT>(mo4 + i, mv[r]);
-            st<NT>(vo4 + i, vv[r]);
+            st<NTS>(po4 + i, pv[r]);
+            st<NTS>(mo4 + i, mv[r]);
+            st<NTS>(vo4 + i, vv[r]);
             if (out2) {
                 u32x2 w;
                 w.x = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
                 w.y = bf16_rne(pv[r].z) | (bf16_rne(pv[r].w) << 16);
-                st<NT>(out2 + i, w);
+                st<NTS>(out2 + i, w);
             }
         }
     }
@@ -203,7 +227,7 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
 // The new state goes to po, mo, vo: the same arrays for the in-place step, or other arrays
 // of the same alignment (the offloaded step reads staged copies and writes host memory).
 // Each element is read before it is written and by the same lane, so p == po needs no care.
-template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
+template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH>
 __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(const float *p, const float *m, const float *v,
                                                          float *po, float *mo, float *vo,
                                                          const void *__restrict__ g,
@@ -293,7 +317,7 @@ struct VecLaunch {
     DevCtl ctl;
 };
 
-template <int ROWS, int BLOCK, bool G_BF16, bool NT, int ARITH>
+template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH>
 static void launch_vec(const VecLaunch &a)
 {
     hipLaunchKernelGGL((adam_vec_kernel<ROWS, BLOCK, G_BF16, NT, ARITH>), a.grid, dim3(BLOCK), a.lds,
@@ -301,7 +325,7 @@ static void launch_vec(const VecLaunch &a)
                        a.ctl);
 }
 
-template <int ROWS, int BLOCK, bool G_BF16, bool NT>
+template <int ROWS, int BLOCK, bool G_BF16, int NT>
 static void pick_arith(int arith, const VecLaunch &a)
 {
     if (arith == 0)
@@ -312,20 +336,24 @@ static void pick_arith(int arith, const VecLaunch &a)
         launch_vec<ROWS, BLOCK, G_BF16, NT, 2>(a);
 }
 
-template <int ROWS, int BLOCK>
-static void pick_flags(bool g_bf16, bool nt, int arith, const VecLaunch &a)
+template <int ROWS, int BLOCK, bool G_BF16>
+static void pick_nt(int nt, int arith, const VecLaunch &a)
 {
-    if (g_bf16) {
-        if (nt) pick_arith<ROWS, BLOCK, true, true>(arith, a);
-        else pick_arith<ROWS, BLOCK, true, false>(arith, a);
-    } else {
-        if (nt) pick_arith<ROWS, BLOCK, false, true>(arith, a);
-        else pick_arith<ROWS, BLOCK, false, false>(arith, a);
-    }
+    if (nt == 0) pick_arith<ROWS, BLOCK, G_BF16, 0>(arith, a);
+    else if (nt == 1) pick_arith<ROWS, BLOCK, G_BF16, 1>(arith, a);
+    else if (nt == 2) pick_arith<ROWS, BLOCK, G_BF16, 2>(arith, a);
+    else pick_arith<ROWS, BLOCK, G_BF16, 3>(arith, a);
+}
+
+template <int ROWS, int BLOCK>
+static void pick_flags(bool g_bf16, int nt, int arith, const VecLaunch &a)
+{
+    if (g_bf16) pick_nt<ROWS, BLOCK, true>(nt, arith, a);
+    else pick_nt<ROWS, BLOCK, false>(nt, arith, a);
 }
 
 template <int BLOCK>
-static void pick_rows(int rows, bool g_bf16, bool nt, int arith, const VecLaunch &a)
+static void pick_rows(int rows, bool g_bf16, int nt, int arith, const VecLaunch &a)
 {
     if (rows == 1) pick_flags<1, BLOCK>(g_bf16, nt, arith, a);
     else if (rows == 2) pick_flags<2, BLOCK>(g_bf16, nt, arith, a);
@@ -425,11 +453,14 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
         // Resident-wave cap: the caller's, else the knob's, else (knob at -1) what measured
-        // best per variant: 12 waves per CU with bf16 gradients and the fused bf16 copy,
-        // 10 for the other three combinations.
+        // best on N(0, sigma) data with one-wave workgroups of one row: 12 waves per CU with
+        // bf16 gradients, 11 with fp32 gradients (one more 16-byte load per lane in flight),
+        // and one wave more for partitions of 2^32 elements and beyond.  Below the optimum
+        // the kernel is latency-bound, above it the eight read and write streams start to
+        // evict each other's open DRAM pages.
         int cap = waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu;
         if (cap < 0)
-            cap = (g_bf16 && bf16_out) ? 12 : 10;
+            cap = (g_bf16 ? 12 : 11) + (n >= (int64_t(1) << 32) ? 1 : 0);
         ZC_TRY(occupancy_cap_lds(cap, block, &lds));
         VecLaunch a{dim3(1), lds, stream, p, m, v, po, mo, vo, g, bf16_out, n, 0, s, ctl};
         const int64_t kMaxGrid = t.launch_max_grid;
@@ -437,9 +468,9 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             a.grid = dim3((unsigned)count);
             a.tile0 = tile0;
-            if (block == 64) pick_rows<64>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
-            else if (block == 128) pick_rows<128>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
-            else pick_rows<256>(rows, g_bf16, t.adam_nontemporal != 0, arith, a);
+            if (block == 64) pick_rows<64>(rows, g_bf16, (int)t.adam_nontemporal, arith, a);
+            else if (block == 128) pick_rows<128>(rows, g_bf16, (int)t.adam_nontemporal, arith, a);
+            else pick_rows<256>(rows, g_bf16, (int)t.adam_nontemporal, arith, a);
         }
     }
     ZC_HIP(hipGetLastError());

@@ -27,9 +27,11 @@ zc_status hip_fail(hipError_t e, const char *what)
 
 void clear_error() { g_err[0] = '\0'; }
 
+// One set of knobs per calling thread: a sweep on one thread never changes the kernels another
+// thread launches, and a thread that never calls zc_tune_set always launches the defaults.
 Tune &tune()
 {
-    static Tune t;
+    static thread_local Tune t;
     return t;
 }
 
@@ -129,7 +131,7 @@ static const Knob kKnobs[] = {
     {"adam.rows", &Tune::adam_rows, 1, 4},
     {"adam.block", &Tune::adam_block, 64, 256},
     {"adam.waves_per_cu", &Tune::adam_waves_per_cu, -1, 64},
-    {"adam.nontemporal", &Tune::adam_nontemporal, 0, 1},
+    {"adam.nontemporal", &Tune::adam_nontemporal, 0, 3},
     {"adam.arith", &Tune::adam_arith, 0, 2},
     {"copy.waves_per_cu", &Tune::copy_waves_per_cu, 0, 64},
     {"cast.waves_per_cu", &Tune::cast_waves_per_cu, 0, 64},

@@ -28,8 +28,8 @@ void clear_error();
     } while (0)
 
 struct Tune {
-    int64_t adam_rows = 2;
-    int64_t adam_block = 128;
+    int64_t adam_rows = 1;
+    int64_t adam_block = 64;
     int64_t adam_waves_per_cu = -1;   // -1: chosen per variant at launch
     int64_t adam_nontemporal = 1;
     int64_t adam_arith = 2;

@@ -57,10 +57,10 @@ def run_both(n, steps, *, g_bf16, mode=zc.ADAMW, grad_scale=1.0, with_out=True, 
     return (host_f32(dp), host_f32(dm), host_f32(dv), host_u16(dout)), (p, m, v, out)
 
 
-def check(gpu, cpu, with_out=True, tag="", steps=10, m_floor=1e-4):
+def check(gpu, cpu, with_out=True, tag="", steps=10, m_floor=1e-4, **bars):
     gp, gm, gv, gout = gpu
     op, om, ov, oout = cpu
-    assert_state_close(gp, gm, gv, op, om, ov, tag=tag, steps=steps, m_floor=m_floor)
+    assert_state_close(gp, gm, gv, op, om, ov, tag=tag, steps=steps, m_floor=m_floor, **bars)
     if with_out:
         # the bf16 copy is RNE of the GPU's own stored p (same decision, same precision) ...
         assert np.array_equal(gout, oracle.cast_bf16(gp)), f"{tag}: fused cast is not RNE of p"
@@ -367,8 +367,11 @@ def test_groups_and_device_side_clipping():
         c = oracle.clip_scale(want32, 0.05, 1.0 / loss_scale)
         assert ulp_diff(np.float32(scale.item()), c) <= 2 and float(c) < 1.0 / loss_scale   # it did clip
         oracle.adam_step_groups(p, m, v, g, ranges=ranges, step=t, grad_scale_dev=c, bf16_out=out, **hpd)
+    # two independent chains: the scale may differ by 2 ulp, so m and v follow it (6 ulp covers
+    # v's square plus rounding); in p the scale cancels up to those roundings, which move the
+    # lr-sized term by a few ulp of lr per step (3 * steps + 2 at max(|p|, lr))
     check((host_f32(dp), host_f32(dm), host_f32(dv), host_u16(dout)), (p, m, v, out), tag="groups",
-          steps=3, m_floor=1e-5)
+          steps=3, m_floor=1e-5, p_ulp=11, mv_ulp=6)
     # bit-identical to stretch-by-stretch calls of the plain entry point
     a = [dev_f32(synth.host_params(n, 51)), dev_f32(np.zeros(n)), dev_f32(np.zeros(n))]
     b = [x.clone() for x in a]
@@ -507,9 +510,12 @@ def test_extreme_magnitudes_one_step(mode, eps, arith):
         assert np.array_equal(np.sign(a[inf]), np.sign(b[inf])), f"{name}: sign of inf differs"
         fin = np.isfinite(b)
         worst = ulp_diff(a[fin], b[fin]).max(initial=0)
-        # one step in double on both sides: at most the rounding of one fused multiply-add
-        # apart; the fp32 variants round the root, the quotient and the products as well
-        assert worst <= (2 if arith == 2 else 6), f"{name}: {worst} ulp apart on finite values (arith {arith})"
+        # one step in double on both sides: m and v are the same expression evaluated the
+        # same way (identical), p differs in its algebra by a few double ulps (one fp32
+        # rounding at most, two where that crosses a binade); the fp32 variants round the
+        # root, the quotient and the products as well
+        bar = (0 if name in ("m", "v") else 2) if arith == 2 else 6
+        assert worst <= bar, f"{name}: {worst} ulp apart on finite values (arith {arith})"
     assert (np.isnan(op).sum() > 0) == (eps == 0.0) or mode == zc.ADAM_L2   # 0/0 only without eps
     # the bf16 copy is RNE of whatever p the GPU stored, NaN and inf included
     assert np.array_equal(go, oracle.cast_bf16(gp))

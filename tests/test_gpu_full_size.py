@@ -37,6 +37,7 @@ def alloc_state(n, g_dtype):
 
 
 def run_windowed(n, steps, with_out, wins):
+    """`steps` AdamW steps over n elements; the oracle follows on the windows."""
     p, m, v, g = alloc_state(n, torch.bfloat16)
     out = torch.zeros(n, dtype=torch.int16, device=DEV) if with_out else None
     host = [(host_f32(p[s:s + w]).copy(), np.zeros(w, np.float32), np.zeros(w, np.float32),
@@ -51,7 +52,7 @@ def run_windowed(n, steps, with_out, wins):
         print(f"step {t} done", flush=True)
     for (s, w), (hp_, hm_, hv_, ho_) in zip(wins, host):
         gp, gm, gv = host_f32(p[s:s + w]), host_f32(m[s:s + w]), host_f32(v[s:s + w])
-        assert_state_close(gp, gm, gv, hp_, hm_, hv_, tag=f"window@{s}")
+        assert_state_close(gp, gm, gv, hp_, hm_, hv_, steps=steps, tag=f"window@{s}")
         if with_out:
             go = host_u16(out[s:s + w])
             assert np.array_equal(go, oracle.cast_bf16(gp)), f"window@{s}: fused cast"
@@ -71,11 +72,12 @@ def test_llama8b_shard_ten_steps():
 
 
 def test_llama70b_shard_step_and_cast():
-    """Llama-3-70B one-of-8 shard: n = 8,819,213,312 (p/m/v ~105 GB resident), fused bf16 copy."""
+    """Llama-3-70B one-of-8 shard: n = 8,819,213,312 (p/m/v ~105 GB resident), fused bf16 copy,
+    the 10 steps the fp32 acceptance bar is defined over."""
     _, shard, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_70B), 8, 1)
     assert shard == 8_819_213_312
     wins = windows_for(shard, extra_boundaries=[shard // 2], seed=3)
-    p, m, v, g, out = run_windowed(shard, 2, True, wins)
+    p, m, v, g, out = run_windowed(shard, 10, True, wins)
     # property at full size: the bf16 copy is torch's RNE narrowing of the stored p, chunked
     step = 1 << 28
     for s in range(0, shard, step * 8):          # every 8th chunk
@@ -153,6 +155,70 @@ def test_mixtral_unshard_full_size():
     assert straddle >= 7
     plan.destroy()
     del outs, gathered
+    torch.cuda.empty_cache()
+
+
+def test_mixtral_step_cast_into_rank_slot_then_unshard():
+    """Config 5 as stated: AdamW + bf16 copy on rank 0's Mixtral-8x7B partition (S' = 5,837,852,672
+    elements, padded to 4096), the copy written straight into rank 0's slot of the gathered buffer
+    of 8 x S' elements whose other seven slots hold the index hash, then the unshard into the 995
+    tensors.  Tensors (and parts of tensors) inside rank 0's slot must be RNE of the updated p,
+    everything else the hash of its own index; p, m, v against the oracle on windows.
+    Allocation is phased: m, v and g are released before the destinations are allocated."""
+    shape = synth.MIXTRAL_8X7B
+    tensors = synth.tensor_list(shape)
+    numels = synth.tensor_numels(shape)
+    offs, shard, total = zc.flat_layout(numels, 8, 4096)
+    assert shard == 5_837_852_672 and 8 * shard - total == 8 * 3584
+    n = shard
+    gathered = torch.empty(8 * shard, dtype=torch.int16, device=DEV)
+    synth.device_index_hash16_(gathered)
+    send = gathered[:n]
+    p, m, v, g = alloc_state(n, torch.bfloat16)
+    wins = windows_for(n, extra_boundaries=[n // 3], count=12, seed=11)
+    host = [(host_f32(p[s:s + w]).copy(), np.zeros(w, np.float32), np.zeros(w, np.float32),
+             np.zeros(w, np.uint16)) for s, w in wins]
+    steps = 2
+    for t in range(1, steps + 1):
+        synth.device_normal_(g, synth.G_STD, seed=2000 + t)
+        zc.adam_step(p, m, v, g, zc.BF16, n, zc.hparams(step=t, **HP), bf16_out=send)
+        sync()
+        for (s, w), (hp_, hm_, hv_, ho_) in zip(wins, host):
+            oracle.adam_step(hp_, hm_, hv_, host_u16(g[s:s + w]), step=t, bf16_out=ho_, **HP)
+        print(f"step {t} done", flush=True)
+    for (s, w), (hp_, hm_, hv_, ho_) in zip(wins, host):
+        gp, gm, gv = host_f32(p[s:s + w]), host_f32(m[s:s + w]), host_f32(v[s:s + w])
+        assert_state_close(gp, gm, gv, hp_, hm_, hv_, steps=steps, tag=f"window@{s}")
+        assert np.array_equal(host_u16(send[s:s + w]), oracle.cast_bf16(gp)), f"window@{s}: fused cast"
+    # the step must not have touched the other ranks' slots
+    edge = synth.device_index_hash16_values(n, 1 << 20, DEV)
+    assert torch.equal(gathered[n:n + (1 << 20)], edge)
+    del m, v, g, edge
+    torch.cuda.empty_cache()
+    outs = [torch.empty(dims, dtype=torch.bfloat16, device=DEV) for _, dims in tensors]
+    plan = zc.unshard_plan_create([(o, t, k) for o, t, k in zip(offs, outs, numels)], 8 * shard)
+    zc.unshard(plan, gathered)
+    sync()
+    print("unshard done", flush=True)
+    straddlers = 0
+    for i, (o, t, k) in enumerate(zip(offs, outs, numels)):
+        flat = t.view(torch.int16).reshape(-1)
+        mine = max(0, min(o + k, n) - o)          # leading elements that lie in rank 0's slot
+        if mine:                                   # torch's bf16 narrowing as the RNE calculator
+            assert torch.equal(flat[:mine], p[o:o + mine].to(torch.bfloat16).view(torch.int16)), tensors[i][0]
+        if mine < k:
+            assert torch.equal(flat[mine:], synth.device_index_hash16_values(o + mine, k - mine, DEV)), tensors[i][0]
+        straddlers += 0 < mine < k
+    assert straddlers == 1                          # exactly one tensor crosses the end of rank 0's slot
+    # sampled rank-0 tensors against the oracle's own cast and copy
+    rng = np.random.default_rng(13)
+    mine_idx = [i for i, (o, k) in enumerate(zip(offs, numels)) if o + k <= n]
+    for i in [mine_idx[0], mine_idx[-1]] + [int(x) for x in rng.choice(mine_idx, 4)]:
+        o, w = offs[i], min(numels[i], 1 << 16)
+        want = oracle.unshard(oracle.cast_bf16(host_f32(p[o:o + w])), [0], [w])[0]
+        assert np.array_equal(host_u16(outs[i].reshape(-1)[:w]), want), tensors[i][0]
+    plan.destroy()
+    del outs, gathered, send, p
     torch.cuda.empty_cache()
 
 

@@ -140,6 +140,31 @@ def test_tune_knobs():
     zc.tune_set("adam.rows", old)
 
 
+def test_tune_knobs_belong_to_the_calling_thread():
+    """A knob set on one thread is invisible to every other thread: a sweep running beside
+    production launches cannot change their kernels."""
+    import threading
+    default = zc.tune_get("adam.block")
+    seen = {}
+
+    def other():
+        seen["before"] = zc.tune_get("adam.block")
+        zc.tune_set("adam.block", 64 if default != 64 else 256)
+        seen["after"] = zc.tune_get("adam.block")
+
+    t = threading.Thread(target=other)
+    t.start()
+    t.join()
+    assert seen["before"] == default and seen["after"] != default
+    assert zc.tune_get("adam.block") == default            # this thread saw nothing
+    zc.tune_set("adam.block", 256 if default != 256 else 64)
+    t = threading.Thread(target=lambda: seen.__setitem__("fresh", zc.tune_get("adam.block")))
+    t.start()
+    t.join()
+    assert seen["fresh"] == default                         # a new thread starts from the defaults
+    zc.tune_set("adam.block", default)
+
+
 @pytest.mark.parametrize("align", [1, 8, 4096])
 def test_flat_layout_matches_oracle_layout(align):
     for numels in ([1, 3, 7, 4097], [0, 9, 0, 2], [], [4096] * 5 + [17],
