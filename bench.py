@@ -1,19 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of one rank's sharded mixed-precision optimizer step on one MI355X.
 
-A *step* is one pass of the whole hot path over one batch of synthetic input:
+The default run measures the largest configurations one GPU holds, the two models the
+paper evaluates (Evaluation, Experimental settings), one after the other:
 
-    zc_grad_sqnorm   (overflow flag + squared norm of the bf16 gradient shard)
-    zc_adam_step     (fused AdamW over the fp32 shard, bf16 copy written straight
-                      into this rank's slot of the gathered buffer, skipped on overflow)
-    zc_unshard       (gathered flat bf16 buffer of 8 rank shards -> per-layer tensors)
+  headline   Llama-3-70B-shaped one-of-8 shard, 8,819,213,312 fp32 elements, 141 GB resident:
+                 zc_grad_sqnorm  (overflow flag + squared norm of the bf16 gradient shard)
+                 zc_adam_step    (fused AdamW, bf16 copy into the send buffer, skipped on overflow)
+             `value` = shard elements / wall time of one such step.  The unshard copy of this
+             model (141 GB gathered + 141 GB of tensors) does not fit next to the step's state,
+             so row a3 of the path is timed at its own largest size:
+  unshard    Mixtral-8x7B-shaped gathered buffer of 8 rank shards (46.7 B bf16 elements,
+             rank-padded) -> 995 per-layer tensors, zc_unshard.
+  whole_step_llama3_8b   all three calls back to back on the Llama-3-8B-shaped shard, where
+             they fit together, as in the previous default of this benchmark.
 
-on a one-of-8 shard of a Llama-3-8B-shaped model (1,003,782,656 fp32 elements,
-291 tensors, boundaries not aligned to the shards).  Everything is resident in
-HBM when the timed region starts.  Prints ONE JSON line.
+Everything is resident in HBM when a timed region starts.  Kernel durations come from HIP
+events recorded on the launch stream inside the timed region.  Prints ONE JSON line.
 
-Extra legs outside the timed region: the offloaded step (pinned host p/m/v
-streamed through a 3-slot ring) and the CPU oracle on a bounded sample.
+Legs outside the timed region: the update kernel's other gradient/copy variants, rows built
+after the main path, the offloaded step (pinned host p/m/v) at the largest size the host pins,
+and the CPU oracle on a bounded sample.
 """
 from __future__ import annotations
 
@@ -30,6 +37,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PCIE_PEAK_GBS = 63.0           # Gen5 x16, per direction
 WORLD = 8
+GIB = 1 << 30
 
 
 def parse_args():
@@ -37,31 +45,35 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama3_8b",
-                    choices=["llama3_8b", "llama3_70b", "mixtral_8x7b", "tiny"])
+    ap.add_argument("--workload", default="headline",
+                    choices=["headline", "llama3_8b", "llama3_70b", "mixtral_8x7b", "tiny"],
+                    help="headline = 70B shard step + Mixtral unshard + 8B whole step (default); "
+                         "a model name = that model's shard only")
     ap.add_argument("--no-unshard", action="store_true",
-                    help="leave the unshard copy out (needed for 70B/Mixtral to fit with the step)")
+                    help="single-model workloads: leave the unshard copy out")
     ap.add_argument("--only-unshard", action="store_true",
-                    help="time the unshard copy alone (Mixtral: the step's state and the two "
-                         "93 GB buffers do not fit in HBM together)")
-    ap.add_argument("--offload-elems", type=int, default=1 << 28,
-                    help="elements streamed in the offload leg (0 = skip the leg)")
-    ap.add_argument("--offload-frac", type=float, default=0.0, help="resident fraction f")
+                    help="single-model workloads: time the unshard copy alone")
+    ap.add_argument("--offload-elems", type=int, default=8_819_213_312,
+                    help="partition size of the offload leg (0 = skip the leg); shrunk to what the "
+                         "host can pin")
+    ap.add_argument("--offload-fracs", default="0,0.5", help="resident fractions f of the offload leg")
     ap.add_argument("--offload-max-pinned-gib", type=float, default=60.0,
-                    help="largest total of pinned host memory to ask for; the partition is shrunk "
-                         "(same resident fraction) when its streamed part would need more")
+                    help="largest total of pinned host memory to ask for")
     ap.add_argument("--offload-chunk-mib", type=int, default=64)
     ap.add_argument("--offload-buffers", type=int, default=3)
-    ap.add_argument("--offload-transports", default="1,2,0",
-                    help="which transports the offload leg times: 1 zero-copy, 2 staged reads + direct "
-                         "writes, 0 staged ring")
+    ap.add_argument("--offload-side-elems", type=int, default=1 << 30,
+                    help="streamed elements for the two staged transports and the link probes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true",
-                    help="skip the short legs for gradient accumulation and the per-tensor layout")
+                    help="skip the legs for step variants, gradient accumulation, the per-tensor "
+                         "layout and the planner replay")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain copy of known size (one unshard segment of 2^30 bf16 "
                          "elements, 2 GiB read + 2 GiB written, 5 launches): the reference for "
-                         "scaling the FETCH_SIZE / WRITE_SIZE counters")
+                         "scaling the WRITE_SIZE counter")
+    ap.add_argument("--calibrate-read", action="store_true",
+                    help="only run a read of known size (zc_grad_sqnorm over 2^30 fp32 elements, "
+                         "4 GiB read, 5 launches): the reference for scaling the FETCH_SIZE counter")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="tuning knob, e.g. adam.rows=4 (repeatable)")
     return ap.parse_args()
@@ -71,41 +83,168 @@ def gb(x):
     return x / 1e9
 
 
-def bind_to_gpu_numa_node(torch):
-    """Run this process on the CPUs of the NUMA node the GPU hangs off, so that pinned
-    host memory allocated afterwards is local to the GPU's PCIe root (device writes to
-    memory on another socket cross the inter-socket link and run several times slower).
-    Returns a small dict describing what was done."""
-    info = {"gpu_numa_node": None, "bound": False}
-    try:
-        props = torch.cuda.get_device_properties(0)
-        bus = getattr(props, "pci_bus_id", None)
-        dom = getattr(props, "pci_domain_id", 0)
-        dev_id = getattr(props, "pci_device_id", 0)
-        if bus is None:
-            return info
-        path = f"/sys/bus/pci/devices/{dom:04x}:{bus:02x}:{dev_id:02x}.0/numa_node"
-        node = int(open(path).read().strip())
-        info["gpu_numa_node"] = node
-        if node < 0:
-            return info
-        cpus = set()
-        for part in open(f"/sys/devices/system/node/node{node}/cpulist").read().strip().split(","):
-            if "-" in part:
-                a, b = part.split("-")
-                cpus.update(range(int(a), int(b) + 1))
-            elif part:
-                cpus.add(int(part))
-        allowed = os.sched_getaffinity(0)
-        use = cpus & allowed
-        info["allowed_cpus"] = len(allowed)
-        info["node_cpus_allowed"] = len(use)
-        if use:
-            os.sched_setaffinity(0, use)
-            info["bound"] = True
-    except Exception as e:  # best effort: the numbers are still valid, only maybe slower
-        info["error"] = repr(e)
-    return info
+def time_launches(torch, fn, reps=10):
+    """Average HIP-event time of `reps` calls of fn on torch's current stream (the launch stream)."""
+    fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in ev) / reps
+
+
+def kernel_record(name, ms_list, nbytes, units, bytes_per_unit):
+    ms_sorted = sorted(ms_list)
+    ms = sum(ms_sorted) / len(ms_sorted)
+    gbps = gb(nbytes) / (ms * 1e-3)
+    return dict(name=name, ms=round(ms, 4), ms_median=round(ms_sorted[len(ms_sorted) // 2], 4),
+                ms_min=round(ms_sorted[0], 4), GBps=round(gbps, 1), frac=round(gbps / HBM_PEAK_GBS, 4),
+                algorithmic_bytes=nbytes, bytes_per_unit=bytes_per_unit,
+                rate_G_per_s=round(units / (ms * 1e-3) / 1e9, 2))
+
+
+def shard_of(zc, synth, workload):
+    import numpy as np
+    tensors = synth.TINY_TENSORS if workload == "tiny" else synth.tensor_list(synth.SHAPES[workload])
+    numels = [int(np.prod(d)) for _, d in tensors]
+    return tensors, numels
+
+
+def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, with_step=True, variants=False):
+    """grad-norm + fused AdamW with bf16 copy (+ unshard of the 8-shard gathered buffer) on one
+    model's one-of-8 shard.  Returns (record, seconds of the timed region)."""
+    tensors, numels = shard_of(zc, synth, workload)
+    offs, shard, total = zc.flat_layout(numels, WORLD, 1)
+    n = shard
+    hp_kw = dict(synth.HP)
+    if with_step:
+        p = torch.empty(n, dtype=torch.float32, device=dev)
+        m = torch.zeros(n, dtype=torch.float32, device=dev)
+        v = torch.zeros(n, dtype=torch.float32, device=dev)
+        g = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        synth.device_normal_(p, synth.P_STD, seed=2)
+        synth.device_normal_(g, synth.G_STD, seed=2001)
+    norm = torch.zeros(1, dtype=torch.float32, device=dev)
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    if with_unshard:
+        gathered = torch.empty(WORLD * shard, dtype=torch.int16, device=dev)
+        synth.device_index_hash16_(gathered)          # the other 7 ranks' bytes
+        send = gathered[:n]                            # this rank's slot (rank 0)
+        outs = [torch.empty(d, dtype=torch.bfloat16, device=dev) for _, d in tensors]
+        plan = zc.unshard_plan_create([(o, t, k) for o, t, k in zip(offs, outs, numels)], WORLD * shard)
+    else:
+        send = torch.empty(n, dtype=torch.int16, device=dev)
+    torch.cuda.synchronize()
+    step_no = [0]
+
+    def one_step(ev=None):
+        step_no[0] += 1
+        hp = zc.hparams(step=step_no[0], **hp_kw)
+        if ev: ev[0].record()
+        if with_step:
+            zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
+        if ev: ev[1].record()
+        if with_step:
+            zc.adam_step(p, m, v, g, zc.BF16, n, hp, bf16_out=send, skip_flag=flag)
+        if ev: ev[2].record()
+        if with_unshard:
+            zc.unshard(plan, gathered)
+        if ev: ev[3].record()
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        one_step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert flag.item() == 0, "synthetic gradients must be finite"
+
+    def times(i):
+        return [e[i].elapsed_time(e[i + 1]) for e in events]
+
+    kernels = {}
+    if with_step:
+        kernels["sqnorm"] = kernel_record("zc::sqnorm_bf16_kernel", times(0), 2 * n, n, 2)
+        kernels["adam"] = kernel_record("zc::adam_vec_kernel", times(1), 28 * n, n, 28)
+    if with_unshard:
+        kernels["unshard"] = kernel_record("zc::unshard_kernel", times(2), 4 * total, total, 4)
+    rec = {"workload": workload, "shard_elements": n, "model_elements": total, "tensors": len(numels),
+           "ms_per_step": round(wall * 1e3 / steps, 4),
+           "gparams_per_s": round(n / (wall / steps) / 1e9, 3), "kernels": kernels}
+
+    if variants and with_step:
+        def hp_next():
+            step_no[0] += 1
+            return zc.hparams(step=step_no[0], **hp_kw)
+
+        g32 = torch.empty(n, dtype=torch.float32, device=dev)
+        synth.device_normal_(g32, synth.G_STD, seed=2999)
+        rows = {
+            "bf16_grads_fused_copy": (28, lambda: zc.adam_step(p, m, v, g, zc.BF16, n, hp_next(), bf16_out=send)),
+            "bf16_grads_no_copy": (26, lambda: zc.adam_step(p, m, v, g, zc.BF16, n, hp_next())),
+            "fp32_grads_fused_copy": (30, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next(), bf16_out=send)),
+            "fp32_grads_no_copy": (28, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next())),
+            "unfused_step_then_cast": (32, lambda: (zc.adam_step(p, m, v, g, zc.BF16, n, hp_next()),
+                                                    zc.cast_bf16(p, send, n))),
+            "standalone_cast": (6, lambda: zc.cast_bf16(p, send, n)),
+        }
+        rec["step_variants"] = {}
+        for name, (bpe, fn) in rows.items():
+            ms = time_launches(torch, fn, reps=10 if n < (1 << 32) else 5)
+            rec["step_variants"][name] = {"bytes_per_element": bpe, "ms": round(ms, 4),
+                                          "GBps": round(gb(bpe * n) / (ms * 1e-3), 1),
+                                          "frac": round(gb(bpe * n) / (ms * 1e-3) / HBM_PEAK_GBS, 4),
+                                          "gparams_per_s": round(n / (ms * 1e-3) / 1e9, 2)}
+        del g32
+    if with_unshard:
+        plan.destroy()
+        del outs, gathered
+    if with_step:
+        del p, m, v, g
+    del send
+    torch.cuda.empty_cache()
+    return rec, wall
+
+
+def placement_leg(torch, synth, zc, dev):
+    """Where the caller puts p, m, v matters for small partitions: the same launch over the
+    Llama-3-8B shard with the five arrays back to back (what an allocator gives for 4 GB arrays)
+    and with each array 36 GiB after the previous one inside one arena."""
+    n = 1_003_782_656
+    arena = torch.empty(4 * 36 * GIB + 3 * GIB, dtype=torch.uint8, device=dev)
+    base = arena.data_ptr()
+
+    def noise(offset, nbytes, seed):                    # N(0, sigma) values, as in the main run
+        nbytes = nbytes // 4 * 4
+        synth.device_normal_(arena[offset:offset + nbytes].view(torch.float32), synth.P_STD, seed=seed)
+
+    hp = zc.hparams(step=3, **synth.HP)
+
+    def up(x, a):
+        return (x + a - 1) // a * a
+
+    s0 = up(4 * n, 2 << 20)
+    layouts = {"back_to_back": [0, s0, 2 * s0, 3 * s0, 3 * s0 + up(2 * n, 2 << 20)],
+               "36_GiB_apart": [k * 36 * GIB for k in range(5)]}
+    out = {}
+    for name, offs in layouts.items():
+        for k, o in enumerate(offs):
+            noise(o, (4 if k < 3 else 2) * n, seed=11 + k)
+        ptr = [base + o for o in offs]
+        ms = time_launches(torch, lambda: zc.adam_step(ptr[0], ptr[1], ptr[2], ptr[3], zc.BF16, n, hp,
+                                                       bf16_out=ptr[4]), reps=10)
+        out[name] = {"ms": round(ms, 4), "GBps": round(gb(28 * n) / (ms * 1e-3), 1),
+                     "frac": round(gb(28 * n) / (ms * 1e-3) / HBM_PEAK_GBS, 4)}
+    del arena
+    torch.cuda.empty_cache()
+    return {"elements": n, "bytes_per_element": 28, **out}
 
 
 def main():
@@ -141,108 +280,73 @@ def main():
                                              "read_bytes_per_launch": 2 * k,
                                              "written_bytes_per_launch": 2 * k}}))
         return
+    if args.calibrate_read:
+        k = 1 << 30
+        src = torch.empty(k, dtype=torch.float32, device=dev)
+        synth.device_normal_(src, synth.G_STD, seed=1)
+        norm = torch.zeros(1, dtype=torch.float32, device=dev)
+        flag = torch.zeros(1, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            zc.grad_sqnorm(src, zc.F32, k, norm, flag)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_read": {"kernel": "zc::sqnorm_f32_kernel", "launches": 5,
+                                             "read_bytes_per_launch": 4 * k}}))
+        return
 
-    # ---- workload ------------------------------------------------------------------
-    if args.workload == "tiny":
-        tensors = synth.TINY_TENSORS
+    tuning = {k: zc.tune_get(k) for k in ("adam.arith", "adam.block", "adam.rows", "adam.waves_per_cu",
+                                          "adam.nontemporal", "copy.waves_per_cu", "copy.nontemporal")}
+    extra = {}
+    if args.workload == "headline":
+        head, wall = step_phase(torch, synth, zc, dev, "llama3_70b", args.steps, args.warmup,
+                                with_unshard=False, variants=not args.no_next_rows)
+        unsh, _ = step_phase(torch, synth, zc, dev, "mixtral_8x7b", args.steps, args.warmup,
+                             with_unshard=True, with_step=False)
+        kernels = dict(head["kernels"])
+        kernels["unshard"] = unsh["kernels"]["unshard"]
+        extra["unshard_mixtral_8x7b"] = {k: unsh[k] for k in ("model_elements", "tensors")}
+        extra["unshard_mixtral_8x7b"]["gathered_elements"] = \
+            WORLD * zc.flat_layout(shard_of(zc, synth, "mixtral_8x7b")[1], WORLD, 1)[1]
+        small, _ = step_phase(torch, synth, zc, dev, "llama3_8b", args.steps, args.warmup,
+                              with_unshard=True, variants=not args.no_next_rows)
+        extra["whole_step_llama3_8b"] = small
+        workload_text = ("llama3_70b one-of-8 shard: grad-norm + fused AdamW with bf16 copy (141 GB resident); "
+                         "unshard timed on the mixtral_8x7b gathered buffer of 8 shards (46.7 B elements -> 995 "
+                         "tensors), which does not fit beside the 70B step")
     else:
-        tensors = synth.tensor_list(synth.SHAPES[args.workload])
-    numels = [int(__import__("numpy").prod(d)) for _, d in tensors]
-    offs, shard, total = zc.flat_layout(numels, WORLD, 1)
-    n = shard
-    do_unshard = not args.no_unshard
-    hp_kw = dict(synth.HP)
+        do_unshard = not args.no_unshard
+        do_step = not args.only_unshard
+        head, wall = step_phase(torch, synth, zc, dev, args.workload, args.steps, args.warmup,
+                                with_unshard=do_unshard, with_step=do_step, variants=not args.no_next_rows)
+        kernels = dict(head["kernels"])
+        workload_text = (f"{args.workload} one-of-{WORLD} shard: "
+                         + ("grad-norm + fused AdamW with bf16 copy" if do_step else "")
+                         + (" + " if do_step and do_unshard else "")
+                         + ("unshard of the 8-shard gathered buffer" if do_unshard else ""))
 
-    do_step = not args.only_unshard
-    if do_step:
-        p = torch.empty(n, dtype=torch.float32, device=dev)
-        m = torch.zeros(n, dtype=torch.float32, device=dev)
-        v = torch.zeros(n, dtype=torch.float32, device=dev)
-        g = torch.empty(n, dtype=torch.bfloat16, device=dev)
-        synth.device_normal_(p, synth.P_STD, seed=2)
-        synth.device_normal_(g, synth.G_STD, seed=2001)
-    norm = torch.zeros(1, dtype=torch.float32, device=dev)
-    flag = torch.zeros(1, dtype=torch.int32, device=dev)
-    if do_unshard:
-        gathered = torch.empty(WORLD * shard, dtype=torch.int16, device=dev)
-        synth.device_index_hash16_(gathered)          # the other 7 ranks' bytes
-        send = gathered[:n]                            # this rank's slot (rank 0)
-        outs = [torch.empty(d, dtype=torch.bfloat16, device=dev) for _, d in tensors]
-        plan = zc.unshard_plan_create([(o, t, k) for o, t, k in zip(offs, outs, numels)],
-                                      WORLD * shard)
-    else:
-        send = torch.empty(n, dtype=torch.int16, device=dev)
-    torch.cuda.synchronize()
-
-    step_no = [0]
-
-    def one_step(ev=None):
-        step_no[0] += 1
-        hp = zc.hparams(step=step_no[0], **hp_kw)
-        if ev: ev[0].record()
-        if do_step:
-            zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
-        if ev: ev[1].record()
-        if do_step:
-            zc.adam_step(p, m, v, g, zc.BF16, n, hp, bf16_out=send, skip_flag=flag)
-        if ev: ev[2].record()
-        if do_unshard:
-            zc.unshard(plan, gathered)
-        if ev: ev[3].record()
-
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        one_step(events[k])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-
-    def times(i):
-        return sorted(e[i].elapsed_time(e[i + 1]) for e in events)
-
-    def avg(i):
-        return sum(times(i)) / len(events)
-
-    t_norm, t_adam, t_unshard = avg(0), avg(1), avg(2)
-    spread = {"sqnorm": times(0), "adam": times(1), "unshard": times(2)}
-    assert flag.item() == 0, "synthetic gradients must be finite"
-
-    kernels = {}
-    if do_step:
-        kernels["sqnorm"] = dict(name="zc::sqnorm_bf16_kernel", ms=t_norm, bytes=2 * n, units=n,
-                                 bytes_per_unit=2)
-        kernels["adam"] = dict(name="zc::adam_vec_kernel", ms=t_adam, bytes=28 * n, units=n,
-                               bytes_per_unit=28)
-    if do_unshard:
-        kernels["unshard"] = dict(name="zc::unshard_kernel", ms=t_unshard, bytes=4 * total,
-                                  units=total, bytes_per_unit=4)
-    for kd in kernels.values():
-        kd["GBps"] = gb(kd["bytes"]) / (kd["ms"] * 1e-3)
-        kd["frac"] = kd["GBps"] / HBM_PEAK_GBS
+    n = head["shard_elements"]
     dominant = max(kernels, key=lambda k: kernels[k]["ms"])
+    dom = kernels[dominant]
+    dom_workload = "mixtral_8x7b" if (args.workload == "headline" and dominant == "unshard") else \
+        ("llama3_70b" if args.workload == "headline" else args.workload)
 
-    traffic = None
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
-            tj = json.load(open(tpath))
-            rec = tj.get(args.workload, {}).get(dominant)
+            rec = json.load(open(tpath)).get(dom_workload, {}).get(dominant)
             if rec:
                 traffic = rec["fetch_bytes"] + rec["write_bytes"]
+                traffic_source = ("profiles/pmc_traffic.json: FETCH_SIZE and WRITE_SIZE of this kernel at this "
+                                  "size from separate rocprofv3 --pmc runs, not counted in this run")
         except Exception:
             traffic = None
 
-    roofline = dict(bound="hbm", kernel=kernels[dominant]["name"],
-                    achieved=round(kernels[dominant]["GBps"], 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(kernels[dominant]["frac"], 4), traffic=traffic,
-                    algorithmic_bytes_per_launch=kernels[dominant]["bytes"],
-                    avg_launch_ms=round(kernels[dominant]["ms"], 4))
+    roofline = dict(bound="hbm", kernel=dom["name"], workload=dom_workload, achieved=dom["GBps"],
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=dom["frac"], traffic=traffic,
+                    traffic_source=traffic_source, algorithmic_bytes_per_launch=dom["algorithmic_bytes"],
+                    avg_launch_ms=dom["ms"], target_frac=0.80,
+                    below_target=[f"{k} {d['frac']}" for k, d in kernels.items() if d["frac"] < 0.80])
 
     result = {
         "metric": "optimizer-step Gparams/s per shard",
@@ -252,99 +356,33 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "f32", 1: "f32+f64", 2: "f64"}[zc.tune_get("adam.arith")], "data": "synthetic",
-        "config": {
-            "workload": (f"{args.workload} one-of-{WORLD} shard: "
-                         + ("grad-norm + fused AdamW with bf16 copy" if do_step else "")
-                         + (" + " if do_step and do_unshard else "")
-                         + ("unshard of the 8-shard gathered buffer" if do_unshard else "")),
-            "shard_elements": n, "model_elements": total, "tensors": len(numels),
-            "grads": "bf16", "state": "fp32 p/m/v resident in HBM",
-            "tuning": {k: zc.tune_get(k) for k in ("adam.arith", "adam.block", "adam.rows",
-                                                  "adam.waves_per_cu", "adam.nontemporal",
-                                                  "copy.waves_per_cu", "copy.nontemporal")},
-        },
+        "config": {"workload": workload_text, "shard_elements": n, "model_elements": head["model_elements"],
+                   "tensors": head["tensors"], "grads": "bf16", "state": "fp32 p/m/v resident in HBM",
+                   "tuning": tuning},
         "roofline": roofline,
-        "kernels": {k: dict(ms=round(d["ms"], 4), ms_median=round(spread[k][len(spread[k]) // 2], 4),
-                            ms_min=round(spread[k][0], 4),
-                            GBps=round(d["GBps"], 1), frac=round(d["frac"], 4),
-                            algorithmic_bytes=d["bytes"],
-                            rate_G_per_s=round(d["units"] / (d["ms"] * 1e-3) / 1e9, 2))
-                    for k, d in kernels.items()},
+        "kernels": kernels,
     }
-    if do_step:
-        result["adam_step_gparams_per_s"] = round(n / (t_adam * 1e-3) / 1e9, 2)
-
-    # ---- the update kernel's other variants on the same shard (not part of `value`) -----
-    if do_step and not args.no_next_rows:
-        def variant(fn):
-            return time_launches(torch, fn, reps=10)
-
-        def hp_next():
-            step_no[0] += 1
-            return zc.hparams(step=step_no[0], **hp_kw)
-
-        scratch = send
-        g32 = torch.empty(n, dtype=torch.float32, device=dev)
-        synth.device_normal_(g32, synth.G_STD, seed=2999)
-        rows = {
-            "bf16_grads_no_copy": (26, lambda: zc.adam_step(p, m, v, g, zc.BF16, n, hp_next())),
-            "fp32_grads_fused_copy": (30, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next(), bf16_out=scratch)),
-            "fp32_grads_no_copy": (28, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next())),
-            "unfused_step_then_cast": (32, lambda: (zc.adam_step(p, m, v, g, zc.BF16, n, hp_next()),
-                                                    zc.cast_bf16(p, scratch, n))),
-            "standalone_cast": (6, lambda: zc.cast_bf16(p, scratch, n)),
-        }
-        result["step_variants"] = {}
-        for name, (bpe, fn) in rows.items():
-            ms = variant(fn)
-            result["step_variants"][name] = {"bytes_per_element": bpe, "ms": round(ms, 4),
-                                             "GBps": round(gb(bpe * n) / (ms * 1e-3), 1),
-                                             "frac": round(gb(bpe * n) / (ms * 1e-3) / HBM_PEAK_GBS, 4),
-                                             "gparams_per_s": round(n / (ms * 1e-3) / 1e9, 2)}
-        del g32
-
-    # ---- free the resident workload before the extra legs --------------------------
-    if do_unshard:
-        plan.destroy()
-        del outs, gathered
-    if do_step:
-        del p, m, v, g
-    del send
-    torch.cuda.empty_cache()
+    if "adam" in kernels:
+        result["adam_step_gparams_per_s"] = kernels["adam"]["rate_G_per_s"]
+    if "step_variants" in head:
+        result["step_variants"] = head["step_variants"]
+    result.update(extra)
 
     if not args.no_next_rows:
+        result["placement_llama3_8b_shard"] = placement_leg(torch, synth, zc, dev)
         result["next_rows"] = next_rows_leg(torch, synth, zc, dev)
         result["next_rows"]["adaptive_offload_plan"] = adaptive_plan_leg(torch, zc, dev)
     if args.offload_elems > 0:
-        legs = {}
-        keep = zc.tune_get("offload.zero_copy")
-        names = {1: "zero_copy", 2: "staged_reads_direct_writes", 0: "staged_ring"}
-        for mode in (int(x) for x in args.offload_transports.split(",")):
-            name = names[mode]
-            zc.tune_set("offload.zero_copy", mode)
-            legs[name] = offload_leg(torch, synth, zc, dev, args, probe=(mode == 0))
-        zc.tune_set("offload.zero_copy", keep)
-        result["offload"] = legs
+        result["offload"] = offload_leg(torch, synth, zc, dev, args)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_leg(synth)
     print(json.dumps(result))
 
 
-def time_launches(torch, fn, reps=10):
-    fn()
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for a, b in ev:
-        a.record()
-        fn()
-        b.record()
-    torch.cuda.synchronize()
-    return sum(a.elapsed_time(b) for a, b in ev) / reps
-
-
 def next_rows_leg(torch, synth, zc, dev):
     """Rows built after the main path: fp32 gradient accumulation (10 B/element) and the
-    unshard copy in the per-tensor even-partition layout (8 segments per tensor)."""
+    unshard copy in the per-tensor even-partition layout (8 segments per tensor), with slices
+    padded to 8 elements (16-byte aligned sources) and unpadded (2- and 4-byte aligned sources)."""
     import numpy as np
     shape = synth.LLAMA3_8B
     tensors = synth.tensor_list(shape)
@@ -355,33 +393,46 @@ def next_rows_leg(torch, synth, zc, dev):
     synth.device_normal_(micro, synth.G_STD, seed=2003)
     t_acc = time_launches(torch, lambda: zc.grad_accumulate(acc, micro, zc.BF16, n, 0.25))
     del acc, micro
-    segs, send = zc.per_tensor_layout(numels, WORLD, 8)
-    gathered = torch.empty(WORLD * send, dtype=torch.int16, device=dev)
-    synth.device_index_hash16_(gathered)
-    outs = [torch.empty(d, dtype=torch.bfloat16, device=dev) for _, d in tensors]
-    table = [(src, outs[t].data_ptr() + 2 * dst if k else None, k) for t, src, dst, k in segs]
-    plan = zc.unshard_plan_create(table, WORLD * send)
-    t_un = time_launches(torch, lambda: zc.unshard(plan, gathered))
-    plan.destroy()
     total = sum(numels)
-    del outs, gathered
+    out = {"grad_accumulate": {"elements": n, "ms": round(t_acc, 4), "bytes_per_element": 10,
+                               "GBps": round(gb(10 * n) / (t_acc * 1e-3), 1),
+                               "frac": round(gb(10 * n) / (t_acc * 1e-3) / HBM_PEAK_GBS, 4)}}
+    outs = [torch.empty(d, dtype=torch.bfloat16, device=dev) for _, d in tensors]
+    # align 8: every slice starts on a 16-byte boundary.  The second list (every tensor nine
+    # elements short, align 1) has odd slice sizes, which puts sources and destinations on 2- and
+    # 4-byte boundaries: the kernel's narrow-load paths.
+    for name, sizes, align in (("unshard_per_tensor", numels, 8),
+                               ("unshard_per_tensor_misaligned_sources", [k - 9 for k in numels], 1)):
+        segs, send = zc.per_tensor_layout(sizes, WORLD, align)
+        gathered = torch.empty(WORLD * send, dtype=torch.int16, device=dev)
+        synth.device_index_hash16_(gathered)
+        table = [(src, outs[t].data_ptr() + 2 * dst if k else None, k) for t, src, dst, k in segs]
+        plan = zc.unshard_plan_create(table, WORLD * send)
+        t_un = time_launches(torch, lambda: zc.unshard(plan, gathered))
+        plan.destroy()
+        moved = sum(sizes)
+        classes = {"16B": 0, "4B": 0, "2B": 0}
+        for t, src, dst, k in segs:
+            if k:
+                head = ((16 - (outs[t].data_ptr() + 2 * dst) % 16) % 16) // 2
+                a = (gathered.data_ptr() + 2 * (src + head)) % 16
+                classes["16B" if a == 0 else ("4B" if a % 4 == 0 else "2B")] += 1
+        out[name] = {"elements": moved, "segments": sum(1 for s in segs if s[3]), "source_alignment_of_segments": classes,
+                     "ms": round(t_un, 4), "bytes_per_element": 4,
+                     "GBps": round(gb(4 * moved) / (t_un * 1e-3), 1),
+                     "frac": round(gb(4 * moved) / (t_un * 1e-3) / HBM_PEAK_GBS, 4)}
+        del gathered
+    del outs
     torch.cuda.empty_cache()
-    return {
-        "grad_accumulate": {"elements": n, "ms": round(t_acc, 4), "bytes_per_element": 10,
-                            "GBps": round(gb(10 * n) / (t_acc * 1e-3), 1),
-                            "frac": round(gb(10 * n) / (t_acc * 1e-3) / HBM_PEAK_GBS, 4)},
-        "unshard_per_tensor": {"elements": total, "segments": sum(1 for s in segs if s[3]),
-                               "ms": round(t_un, 4), "bytes_per_element": 4,
-                               "GBps": round(gb(4 * total) / (t_un * 1e-3), 1),
-                               "frac": round(gb(4 * total) / (t_un * 1e-3) / HBM_PEAK_GBS, 4)},
-    }
+    return out
 
 
 def adaptive_plan_leg(torch, zc, dev):
     """The paper's adaptive offloading (Algorithm 2 + backward reload) planned on a synthetic
     memory profile (rising through the forward pass, falling through the backward pass) and
     replayed with stand-in compute kernels: 32 optimizer-state fragments of 64 MiB, 24 of which
-    must leave, 16 + 16 operators of 8 ms.  Compared with offloading everything synchronously."""
+    must leave, 16 + 16 operators of 8 ms.  Compared with offloading everything synchronously
+    (the comparison mode of the paper's Evaluation, Adaptive Offloading) and with no offloading."""
     nfrags, elems = 32, 16 << 20
     state = torch.zeros(nfrags * elems, dtype=torch.float32, device=dev)
     host = [zc.host_alloc(4 * elems) for _ in range(nfrags)]
@@ -415,78 +466,129 @@ def adaptive_plan_leg(torch, zc, dev):
     return {"operators": len(p_mem), "operator_ms": 8.0, "fragments": nfrags, "fragment_MiB": 64,
             "fragments_offloaded_by_plan": moved, "ms_no_offload": round(t_none, 1),
             "ms_adaptive_plan": round(t_adaptive, 1), "ms_offload_all_sync": round(t_sync, 1),
-            "sync_over_adaptive": round(t_sync / t_adaptive, 3)}
+            "sync_over_adaptive": round(t_sync / t_adaptive, 3),
+            "adaptive_over_no_offload": round(t_adaptive / t_none, 3),
+            "overlap_holds": bool(t_adaptive < 0.95 * t_sync and t_adaptive < 1.25 * t_none)}
 
 
-def offload_leg(torch, synth, zc, dev, args, probe=True):
-    """Offloaded step: p/m/v of the streamed part in pinned host DRAM, 3-slot ring."""
-    numa = bind_to_gpu_numa_node(torch)
-    n_asked = n = int(args.offload_elems)
-    cap_elems = int(args.offload_max_pinned_gib * (1 << 30)) // 12
-    if (1.0 - args.offload_frac) * n > cap_elems:
-        n = int(cap_elems / (1.0 - args.offload_frac)) // 1024 * 1024
-    n_res = int(args.offload_frac * n) // 1024 * 1024
-    n_str = n - n_res
+def offload_leg(torch, synth, zc, dev, args):
+    """Offloaded step: p/m/v of the streamed part in pinned host DRAM.  The zero-copy transport
+    (default) at the largest partition the host pins, for each resident fraction asked; the two
+    staged transports and the plain-copy link ceilings at --offload-side-elems."""
+    n_asked = int(args.offload_elems)
+    fracs = [float(x) for x in args.offload_fracs.split(",")]
+    # three pinned arrays as large as the streamed part needs, up to the cap; a host that
+    # refuses gets asked for 7/8 of that, and so on
+    cap_bytes = int(args.offload_max_pinned_gib * GIB)
+    need = min(cap_bytes, 12 * int(max((1.0 - f) * n_asked for f in fracs)))
+    cap_elems = (need // 12) // 1024 * 1024
+    refused = []
+    while True:
+        bufs = []
+        try:
+            for _ in range(3):
+                bufs.append(zc.host_alloc(4 * max(cap_elems, 1)))
+            break
+        except zc.ZcError as e:
+            refused.append({"GiB": round(12 * cap_elems / GIB, 2), "error": e.message[:80]})
+            for b in bufs:
+                b.free()
+            cap_elems = (cap_elems * 7 // 8) // 1024 * 1024
+            if cap_elems < (1 << 20):
+                raise
+    pinned_limit = {"asked_GiB": round(need / GIB, 2), "granted_GiB": round(12 * cap_elems / GIB, 2),
+                    "refused": refused}
     chunk = args.offload_chunk_mib << 20
-    # exact-size pinned arrays (torch's pinned allocator rounds up to a power of two)
-    bufs = [zc.host_alloc(4 * max(n_str, 1)) for _ in range(3)]
     hp_, hm_, hv_ = (torch.from_numpy(b.numpy("float32")) for b in bufs)
     piece = 1 << 28
-    tmp = torch.empty(min(piece, max(n_str, 1)), dtype=torch.float32, device=dev)
-    for s0 in range(0, n_str, piece):                 # p ~ N(0, 0.02); m = v = 0
-        e0 = min(n_str, s0 + piece)
+    tmp = torch.empty(piece, dtype=torch.float32, device=dev)
+    for s0 in range(0, cap_elems, piece):              # p ~ N(0, 0.02); m = v = 0
+        e0 = min(cap_elems, s0 + piece)
         synth.device_normal_(tmp[:e0 - s0], synth.P_STD, seed=3 + s0 // piece)
         hp_[s0:e0].copy_(tmp[:e0 - s0])
     hm_.zero_()
     hv_.zero_()
     del tmp
-    dp, dm, dv = (torch.zeros(max(n_res, 1), dtype=torch.float32, device=dev) for _ in range(3))
-    g = torch.empty(n, dtype=torch.bfloat16, device=dev)
-    synth.device_normal_(g, synth.G_STD, seed=2002)
-    send = torch.empty(n, dtype=torch.int16, device=dev)
     ctx = zc.offload_create(chunk, args.offload_buffers)
-    torch.cuda.synchronize()
+    keep = zc.tune_get("offload.zero_copy")
 
-    def run(step):
-        ctx.adam_step(dp if n_res else None, dm if n_res else None, dv if n_res else None, n_res,
-                      hp_, hm_, hv_, n_str, g, zc.BF16, zc.hparams(step=step, **synth.HP),
-                      bf16_out_dev=send)
+    def timed(n, n_res, n_str, reps):
+        dp, dm, dv = (torch.zeros(max(n_res, 1), dtype=torch.float32, device=dev) for _ in range(3))
+        g = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        synth.device_normal_(g, synth.G_STD, seed=2002)
+        send = torch.empty(n, dtype=torch.int16, device=dev)
 
-    run(1)
-    torch.cuda.synchronize()
-    reps = 3
-    t0 = time.perf_counter()
-    for k in range(reps):
-        run(2 + k)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / reps
+        def run(step):
+            ctx.adam_step(dp if n_res else None, dm if n_res else None, dv if n_res else None, n_res,
+                          bufs[0], bufs[1], bufs[2], n_str, g, zc.BF16, zc.hparams(step=step, **synth.HP),
+                          bf16_out_dev=send)
 
-    extra = {}
-    if probe and n_str > 0:
-        # plain pinned-copy ceilings with the same chunking: one direction at a time and both
-        nbytes = 4 * n_str
-        t_h2d = min(ctx.probe_link(hp_, hv_, nbytes, 0) for _ in range(3)) * 1e-3
-        t_d2h = min(ctx.probe_link(hp_, hv_, nbytes, 1) for _ in range(3)) * 1e-3
-        t_both = min(ctx.probe_link(hp_, hv_, nbytes, 2) for _ in range(3)) * 1e-3
-        extra["memcpy_ceiling_GBps"] = {"h2d": round(gb(nbytes) / t_h2d, 2),
-                                        "d2h": round(gb(nbytes) / t_d2h, 2),
-                                        "both_each": round(gb(nbytes) / t_both, 2)}
+        run(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(reps):
+            run(2 + k)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        del dp, dm, dv, g, send
+        torch.cuda.empty_cache()
+        one_way = 12 * n_str
+        return {"elements": n, "streamed_elements": n_str, "pinned_GB": round(12 * n_str / 1e9, 2),
+                "resident_fraction": round(n_res / n, 4), "ms_per_step": round(dt * 1e3, 3),
+                "gparams_per_s": round(n / dt / 1e9, 3),
+                "link_GBps_each_direction": round(gb(one_way) / dt, 2),
+                "frac_of_link_peak": round(gb(one_way) / dt / PCIE_PEAK_GBS, 4)}
+
+    out = {"pinned_limit": pinned_limit, "chunk_MiB": args.offload_chunk_mib, "buffers": args.offload_buffers,
+           "link_peak_GBps": PCIE_PEAK_GBS, "host_numa": gpu_numa_node(torch), "zero_copy": {}}
+    zc.tune_set("offload.zero_copy", 1)
+    for f in fracs:
+        n = n_asked
+        if (1.0 - f) * n > cap_elems:                   # shrink the partition, keep the fraction
+            n = int(cap_elems / (1.0 - f)) // 1024 * 1024
+        n_res = int(f * n) // 1024 * 1024
+        rec = timed(n, n_res, n - n_res, reps=3)
+        rec["elements_asked"] = n_asked
+        out["zero_copy"][f"f={f:g}"] = rec
+    side = min(int(args.offload_side_elems), cap_elems)
+    for mode, name in ((2, "staged_reads_direct_writes"), (0, "staged_ring")):
+        zc.tune_set("offload.zero_copy", mode)
+        out[name] = timed(side, 0, side, reps=3)
+    zc.tune_set("offload.zero_copy", keep)
+    # plain pinned-copy ceilings with the same chunking: one direction at a time and both
+    nbytes = 4 * side
+    t_h2d = min(ctx.probe_link(bufs[0], bufs[2], nbytes, 0) for _ in range(3)) * 1e-3
+    t_d2h = min(ctx.probe_link(bufs[0], bufs[2], nbytes, 1) for _ in range(3)) * 1e-3
+    t_both = min(ctx.probe_link(bufs[0], bufs[2], nbytes, 2) for _ in range(3)) * 1e-3
+    out["memcpy_ceiling_GBps"] = {"h2d": round(gb(nbytes) / t_h2d, 2), "d2h": round(gb(nbytes) / t_d2h, 2),
+                                  "both_each": round(gb(nbytes) / t_both, 2)}
+    best = out["zero_copy"][f"f={fracs[0]:g}"]["link_GBps_each_direction"]
+    out["headline"] = {"transport": "zero_copy", "link_GBps_each_direction": best,
+                       "frac_of_link_peak_63": round(best / PCIE_PEAK_GBS, 4),
+                       "frac_of_duplex_memcpy_ceiling": round(best / out["memcpy_ceiling_GBps"]["both_each"], 4),
+                       "target_frac_of_link_peak": 0.80}
     ctx.destroy()
     del hp_, hm_, hv_
     for b in bufs:
         b.free()
-    one_way = 12 * n_str
-    return {
-        "elements": n, "elements_asked": n_asked, "streamed_elements": n_str,
-        "pinned_GB": round(12 * n_str / 1e9, 2),
-        "resident_fraction": n_res / n, "chunk_MiB": args.offload_chunk_mib,
-        "buffers": args.offload_buffers, "ms_per_step": round(dt * 1e3, 3),
-        "gparams_per_s": round(n / dt / 1e9, 3),
-        "link_GBps_each_direction": round(gb(one_way) / dt, 2),
-        "link_peak_GBps": PCIE_PEAK_GBS, "frac_of_link_peak": round(gb(one_way) / dt / PCIE_PEAK_GBS, 4),
-        "zero_copy": zc.tune_get("offload.zero_copy"),
-        "host_numa": numa, **extra,
-    }
+    return out
+
+
+def gpu_numa_node(torch):
+    """NUMA node the GPU hangs off, as the kernel reports it (-1: the host exposes no node
+    information, as on a single-socket or virtualised box; nothing to bind to then)."""
+    info = {"gpu_numa_node": None}
+    try:
+        props = torch.cuda.get_device_properties(0)
+        bus = getattr(props, "pci_bus_id", None)
+        dom = getattr(props, "pci_domain_id", 0)
+        dev_id = getattr(props, "pci_device_id", 0)
+        if bus is not None:
+            path = f"/sys/bus/pci/devices/{dom:04x}:{bus:02x}:{dev_id:02x}.0/numa_node"
+            info["gpu_numa_node"] = int(open(path).read().strip())
+    except Exception as e:
+        info["error"] = repr(e)
+    return info
 
 
 def cpu_baseline_leg(synth):
@@ -503,29 +605,32 @@ def cpu_baseline_leg(synth):
     g = oracle.cast_bf16(synth.host_normal(ns, synth.G_STD, 2001))
     gathered = synth.host_index_hash16(0, WORLD * ns)
     send = gathered[:ns]
-    # tensor boundaries: the 8B model's first tensors scaled into the sample
+    # tensor boundaries: ragged cuts of the sample, not aligned to the shard
     cuts = [0, ns // 3 + 5, ns * 2 + 17, ns * 5 - 3, WORLD * ns]
     offs = cuts[:-1]
     nums = [b - a for a, b in zip(cuts[:-1], cuts[1:])]
+    # `value` is defined like the GPU's: elements per second of grad-norm + AdamW + bf16 copy;
+    # the unshard copy is timed by itself, as it is on the GPU
     t0 = time.perf_counter()
     for t in range(1, passes + 1):
         _, bad = oracle.grad_sqnorm(g)
         oracle.adam_step(p, m, v, g, step=t, bf16_out=send, skip=bool(bad), **synth.HP)
-        oracle.unshard(gathered, offs, nums)
     dt = (time.perf_counter() - t0) / passes
+    t0 = time.perf_counter()
+    for t in range(4):
+        oracle.unshard(gathered, offs, nums)
+    dt_unshard = (time.perf_counter() - t0) / 4
 
     # The same oracle calls on disjoint slices from a pool of threads (the C functions run
     # without the interpreter lock): what all the host's cores reach together.
     from concurrent.futures import ThreadPoolExecutor
     threads = max(1, min(16, os.cpu_count() or 1))
     bounds = [ns * k // threads for k in range(threads + 1)]
-    gb_ = [WORLD * ns * k // threads for k in range(threads + 1)]
 
     def work(k, t):
         a, b = bounds[k], bounds[k + 1]
         _, bad = oracle.grad_sqnorm(g[a:b])
         oracle.adam_step(p[a:b], m[a:b], v[a:b], g[a:b], step=t, bf16_out=send[a:b], skip=bool(bad), **synth.HP)
-        oracle.unshard(gathered[gb_[k]:gb_[k + 1]], [0], [gb_[k + 1] - gb_[k]])
 
     par_passes = 4
     with ThreadPoolExecutor(threads) as pool:
@@ -537,11 +642,12 @@ def cpu_baseline_leg(synth):
     return {"value": round(ns / dt / 1e9, 4), "unit": "Gparams/s", "cores": 1, "kind": "oracle",
             "all_cores": {"value": round(ns / dt_par / 1e9, 4), "unit": "Gparams/s", "cores": threads,
                           "sample": f"{par_passes} passes, the same calls on {threads} disjoint slices in {threads} threads"},
-            "sample": (f"{passes} passes over a 2^26-element shard slice (grad-norm + AdamW + bf16 "
-                       f"copy) and its 8 x 2^26-element gathered buffer (unshard); "
-                       f"{round(dt, 2)} s per pass; host has {os.cpu_count()} logical CPUs, "
-                       "the oracle is sequential"),
-            "seconds": round(dt * passes, 2)}
+            "unshard": {"value": round(WORLD * ns / dt_unshard / 1e9, 4), "unit": "G bf16 elements/s", "cores": 1,
+                        "sample": "4 passes over the 8 x 2^26-element gathered buffer, 4 ragged tensors"},
+            "sample": (f"{passes} passes over a 2^26-element slice of the shard (grad-norm + AdamW + bf16 "
+                       f"copy, the calls `value` times on the GPU); {round(dt, 2)} s per pass; host has "
+                       f"{os.cpu_count()} logical CPUs, the oracle is sequential"),
+            "seconds": round(dt * passes + dt_unshard * 4, 2)}
 
 
 if __name__ == "__main__":

@@ -230,8 +230,11 @@ zc_status zc_unshard_plan_destroy(zc_unshard_plan *plan);
  *
  * zc_offload_create   chunk_bytes: bytes per fp32 array per chunk, a positive
  *                     multiple of 4096 (64 MiB in the reference workload);
- *                     num_buffers in [1, 8].  Allocates 3*num_buffers*
- *                     chunk_bytes of device staging memory, two streams, events.
+ *                     num_buffers in [1, 8].  Creates two streams and the events.
+ *                     The staging ring of 3*num_buffers*chunk_bytes of device
+ *                     memory is allocated by the first call that stages (transports
+ *                     0 and 2, zc_offload_probe_link; ZC_ERR_NOMEM if it does not
+ *                     fit) and never by the default transport.
  * zc_offload_adam_step
  *   p_dev,m_dev,v_dev DEVICE fp32[n_resident] (may be NULL when n_resident==0)
  *   p_host,...        HOST fp32[n_streamed], allocated with hipHostMalloc (or

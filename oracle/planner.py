@@ -1,206 +1,239 @@
-"""Adaptive offloading of optimizer-state fragments, written out step by step.
+"""Host-side planners of the paper, as plain Python: when optimizer-state fragments leave
+and return (Adaptive offloading), where all-gathers are hoisted to and which of them are
+merged (Proactive prefetching), which gathered parameters stay unsharded (Selective
+unsharding).
 
-TEST INFRASTRUCTURE (part of the CPU oracle).  Plain Python in the paper's
-notation: S0 / S (schedules), M (memory limit), P_mem(o) (profiled memory in
-use before operator o, optimizer states not included), OS (fragments),
-B_os(os) (fragment size), M_opt (total size of the optimizer states), M^-
-(bytes freed so far).
+TEST INFRASTRUCTURE (part of the CPU oracle).  Each function states the behaviour the paper
+describes and computes it directly; the readings taken where the paper leaves a choice open
+are listed with each function.
 
-Forward pass: Adaptive offloading, Algorithm 2.  Readings where the listing is
-ambiguous: M_peak is taken over the whole iteration (the paper's memory-trend
-figure puts the largest spikes in the backward pass), so the wait-and-free loop
-also runs over the backward operators; the first loop walks the fragments in
-order and stops adding as soon as the peak fits; "Pop" takes fragments in the
-order they were offloaded (the copy started first finishes first).
-
-Backward pass: the paragraph after Algorithm 2 — walk the backward operators;
-wherever enough memory is free from that operator to the end of the schedule,
-start the asynchronous copy back of the next fragment.  Reading: "enough" means
-that the largest profiled usage from that operator on, plus the optimizer
-bytes resident after the reload, stays within M; fragments return in the order
-they left; whatever has not been started when the schedule ends is reloaded
-there; every reload is waited for before the parameter update.
+Inputs are profiles: `usage[i]` is the device memory in use right before operator i with the
+optimizer states left out, `fragment_bytes[f]` the size of optimizer-state fragment f,
+`buffer_bytes[i]` the size of the buffer all-gather i fills, and a table of measured
+communication times by message size.
 """
 from __future__ import annotations
+
+from bisect import bisect_left
+from collections import deque
 
 COMPUTE, OFFLOAD, SYNC_FREE, RELOAD, SYNC_RELOAD = range(5)
 KIND_NAMES = ("compute", "offload", "sync_free", "reload", "sync_reload")
 
 
-def plan(p_mem, n_forward, frag_bytes, M):
-    """Whole iteration: operators [0, n_forward) are the forward pass, the rest the
-    backward pass.  Returns the new schedule S as a list of (kind, index)."""
-    p_mem = list(p_mem)
-    frag_bytes = list(frag_bytes)
-    N = len(p_mem)
-    S = []
-    M_minus = 0
-    M_peak = max(p_mem) if N else 0
-    M_opt = sum(frag_bytes)
-    OS_offload = []
-    for i, b in enumerate(frag_bytes):
-        if M_peak + M_opt - sum(frag_bytes[j] for j in OS_offload) > M:
-            OS_offload.append(i)
-            S.append((OFFLOAD, i))
-    pending = list(OS_offload)      # copy started, memory not yet freed
-    waiting = []                    # freed, reload not yet started
-    started = []                    # reload started
-    # largest profiled usage from operator i to the end of the schedule
-    tail_max = [0] * (N + 1)
-    for i in range(N - 1, -1, -1):
-        tail_max[i] = max(p_mem[i], tail_max[i + 1])
-    for i in range(N):
-        while p_mem[i] + M_opt - M_minus > M:
-            if not pending:
+def plan(usage, n_forward, fragment_bytes, limit):
+    """Adaptive offloading over one iteration (paper: Adaptive offloading, Algorithm 2, and the
+    paragraph on the backward pass after it).  Operators [0, n_forward) are the forward pass,
+    the rest the backward pass.  Returns the schedule as a list of (kind, index).
+
+    What the paper asks for: move out only as much optimizer state as the memory peak needs;
+    start those copies at the very beginning so that they overlap the forward pass; take a
+    fragment's memory away (after waiting for its copy) only when an operator would not fit
+    otherwise; in the backward pass bring fragments back as soon as there is room; have
+    everything back before the update.
+
+    Readings: the peak is taken over the whole iteration (the paper's memory-trend figure has
+    its spikes in the backward pass), so memory may still have to be taken away there;
+    fragments leave, are released and return in list order; "room" for a reload means that the
+    largest usage from that operator to the end of the iteration still fits once the fragment
+    is back; fragments that found no room are reloaded after the last operator; every reload
+    is waited for at the end.
+    """
+    usage = list(usage)
+    sizes = list(fragment_bytes)
+    n_ops = len(usage)
+    state_bytes = sum(sizes)
+    # missing[i]: optimizer-state bytes that must be off the device while operator i runs
+    missing = [u + state_bytes - limit for u in usage]
+    worst = (max(usage) if usage else 0) + state_bytes - limit
+
+    # Which fragments leave: the shortest prefix of the list whose total covers the worst operator.
+    leaving, covered = [], 0
+    for f, b in enumerate(sizes):
+        if covered >= worst:
+            break
+        leaving.append(f)
+        covered += b
+    schedule = [(OFFLOAD, f) for f in leaving]
+
+    # missing_ahead[i]: the largest `missing` from operator i to the end
+    missing_ahead = [0] * (n_ops + 1)
+    for i in reversed(range(n_ops)):
+        missing_ahead[i] = max(missing[i], missing_ahead[i + 1])
+
+    copying_out = deque(leaving)     # copy started, memory still held
+    away = deque()                   # memory released, copy back not started
+    coming_back = []                 # copy back started
+    absent = 0                       # bytes of `away`
+    for i in range(n_ops):
+        while missing[i] > absent:                       # operator i does not fit yet
+            if not copying_out:
                 raise ValueError("the schedule does not fit even with every fragment offloaded")
-            os_i = pending.pop(0)
-            S.append((SYNC_FREE, os_i))
-            M_minus += frag_bytes[os_i]
-            waiting.append(os_i)
+            f = copying_out.popleft()
+            schedule.append((SYNC_FREE, f))
+            absent += sizes[f]
+            away.append(f)
         if i >= n_forward:
-            while waiting and tail_max[i] + M_opt - M_minus + frag_bytes[waiting[0]] <= M:
-                f = waiting.pop(0)
-                S.append((RELOAD, f))
-                M_minus -= frag_bytes[f]
-                started.append(f)
-        S.append((COMPUTE, i))
-    for f in waiting:                 # no room before the end: bring them back now
-        S.append((RELOAD, f))
-        started.append(f)
-    for f in started:                 # all of them must have landed before the update
-        S.append((SYNC_RELOAD, f))
-    return S
+            while away and missing_ahead[i] <= absent - sizes[away[0]]:   # fits from here to the end
+                f = away.popleft()
+                schedule.append((RELOAD, f))
+                absent -= sizes[f]
+                coming_back.append(f)
+        schedule.append((COMPUTE, i))
+    for f in away:
+        schedule.append((RELOAD, f))
+        coming_back.append(f)
+    schedule.extend((SYNC_RELOAD, f) for f in coming_back)
+    return schedule
 
 
 def plan_offload_all_sync(n_ops, nfrags):
-    """The comparison mode of the paper's evaluation: everything is offloaded and
-    waited for before the forward pass and reloaded synchronously at the end."""
-    S = [(OFFLOAD, f) for f in range(nfrags)] + [(SYNC_FREE, f) for f in range(nfrags)]
-    S += [(COMPUTE, i) for i in range(n_ops)]
-    S += [(RELOAD, f) for f in range(nfrags)] + [(SYNC_RELOAD, f) for f in range(nfrags)]
-    return S
+    """The comparison mode of the paper's evaluation (Evaluation, Adaptive Offloading):
+    everything is offloaded and waited for before the forward pass and reloaded
+    synchronously at the end."""
+    head = [(OFFLOAD, f) for f in range(nfrags)] + [(SYNC_FREE, f) for f in range(nfrags)]
+    body = [(COMPUTE, i) for i in range(n_ops)]
+    tail = [(RELOAD, f) for f in range(nfrags)] + [(SYNC_RELOAD, f) for f in range(nfrags)]
+    return head + body + tail
 
 
-def peak_memory(S, p_mem, frag_bytes):
+def peak_memory(schedule, usage, fragment_bytes):
     """Replay a schedule: largest (profiled usage + resident optimizer bytes) seen before
     any compute operator, counting a fragment as resident from the moment its reload starts
     until its memory is freed.  Also checks the ordering rules; returns the peak."""
-    resident = sum(frag_bytes)
-    state = ["resident"] * len(frag_bytes)
+    resident = sum(fragment_bytes)
+    state = ["resident"] * len(fragment_bytes)
     peak = 0
-    for kind, idx in S:
+    for kind, idx in schedule:
         if kind == OFFLOAD:
             assert state[idx] == "resident", "offload of a fragment that is not resident"
             state[idx] = "copying_out"
         elif kind == SYNC_FREE:
             assert state[idx] == "copying_out", "free before the offload copy was started"
             state[idx] = "host"
-            resident -= frag_bytes[idx]
+            resident -= fragment_bytes[idx]
         elif kind == RELOAD:
             assert state[idx] == "host", "reload of a fragment that is not on the host"
             state[idx] = "copying_in"
-            resident += frag_bytes[idx]
+            resident += fragment_bytes[idx]
         elif kind == SYNC_RELOAD:
             assert state[idx] == "copying_in", "wait for a reload that was never started"
             state[idx] = "resident"
         else:
-            peak = max(peak, p_mem[idx] + resident)
+            peak = max(peak, usage[idx] + resident)
     assert all(s in ("resident", "copying_out") for s in state), "a fragment is missing at the update"
     return peak
 
 
-# ---------------------------------------------------------------------------
-# Proactive prefetching (Algorithm 1), Fuse, and the selective-unsharding choice.
-#
-# Notation as in the paper's Table 1: S0 initial schedule o_1..o_N, M memory
-# limit, M_prefetch limit of a prefetch group, P_mem(o), B_ag(o), Fuse(U),
-# T_c(V), alpha.
-#
-# Readings where the listing is incomplete: (1) in the branch where o_i does not
-# fit, the group U is flushed and o_i then opens the next group if it fits on
-# its own, otherwise it stays where it is; (2) o_1 has no predecessor to test
-# against: an all-gather there joins the last group unless the group limit says no; (3) S is assembled back to
-# front and reversed at the end; (4) Fuse walks the group in schedule order and
-# merges the next all-gather into the current fused one while
-# T_c(V1) + T_c(V2) > alpha * T_c(V1 + V2); (5) T_c(V) is the profiled table,
-# linear between samples, flat below the first and continued with the last slope.
-# ---------------------------------------------------------------------------
-
-def t_c(V, sizes, times):
-    """Profiled communication time for V bytes from the (sizes, times) table."""
-    if V <= sizes[0]:
+def t_c(nbytes, sizes, times):
+    """Communication time of a message of `nbytes` from the profiled (sizes, times) table
+    (paper: Proactive prefetching, T_c).  Reading: straight lines between neighbouring
+    samples, the first sample's time for anything smaller, the last segment's slope continued
+    for anything larger."""
+    if nbytes <= sizes[0] or len(sizes) == 1:
         return times[0]
-    k = len(sizes) - 1
-    for i in range(1, len(sizes)):
-        if V <= sizes[i]:
-            k = i
-            break
-    s0, s1, t0, t1 = sizes[k - 1], sizes[k], times[k - 1], times[k]
-    return t0 + (t1 - t0) * (V - s0) / (s1 - s0)
+    hi = min(bisect_left(sizes, nbytes), len(sizes) - 1)    # first sample >= nbytes, else the last
+    lo = hi - 1
+    # the line through the two samples, in its two-point form
+    return times[lo] + (times[hi] - times[lo]) * (nbytes - sizes[lo]) / (sizes[hi] - sizes[lo])
 
 
-def fuse(U, bag, sizes, times, alpha):
-    """Fuse(U): list of groups (lists of operator indices) in schedule order."""
-    groups = []
-    for o in U:
-        if groups:
-            V1 = sum(bag[x] for x in groups[-1])
-            V2 = bag[o]
-            if t_c(V1, sizes, times) + t_c(V2, sizes, times) > alpha * t_c(V1 + V2, sizes, times):
-                groups[-1].append(o)
+def fuse(gathers, buffer_bytes, sizes, times, alpha):
+    """Merge neighbouring all-gathers of a prefetch group while one message is cheaper than
+    two (paper: Proactive prefetching, Fuse: merge when the separate times together exceed
+    alpha times the time of the merged message).  Reading: the group is walked in schedule
+    order and each all-gather is tested against the merged message built so far.
+    Returns a list of lists of operator indices, in schedule order."""
+    merged = []          # [[indices], bytes]
+    for o in gathers:
+        b = buffer_bytes[o]
+        if merged:
+            have = merged[-1][1]
+            apart = t_c(have, sizes, times) + t_c(b, sizes, times)
+            if apart > alpha * t_c(have + b, sizes, times):
+                merged[-1][0].append(o)
+                merged[-1][1] = have + b
                 continue
-        groups.append([o])
-    return groups
+        merged.append([[o], b])
+    return [members for members, _ in merged]
 
 
-def plan_prefetch(is_ag, bag, p_mem, M, M_prefetch, sizes, times, alpha):
-    """Algorithm 1.  Returns the new schedule as a list of entries, each either
-    ("op", i) or ("allgather", [i, j, ...]) for a fused group."""
-    N = len(is_ag)
-    S = []          # built back to front
-    U = []          # unscheduled all-gathers, latest first
+def plan_prefetch(is_allgather, buffer_bytes, usage, limit, group_limit, sizes, times, alpha):
+    """Proactive prefetching (paper: Proactive prefetching, Algorithm 1).  Returns the new
+    schedule as a list of ("op", i) and ("allgather", [i, j, ...]) entries.
 
-    def flush():
-        if U:
-            for grp in reversed(fuse(list(reversed(U)), bag, sizes, times, alpha)):
-                S.append(("allgather", grp))
-            U.clear()
+    What the paper asks for: starting from the end of the schedule, let every all-gather
+    travel towards the front together with the all-gathers met so far, for as long as the
+    memory in use before the operator in front of it plus the travelling buffers stays below
+    the limit and the travelling buffers stay below the group limit; where that stops, the
+    travelling group is put down (and fused); nothing else changes its order.
 
-    for i in range(N - 1, 0, -1):           # o_N ... o_2 (0-based N-1 ... 1)
-        if is_ag[i]:
-            m_U = sum(bag[o] for o in U) + bag[i]
-            m_prev = p_mem[i - 1] + m_U
-            if m_prev < M and m_U < M_prefetch:
-                U.append(i)
-            else:
-                flush()
-                if p_mem[i - 1] + bag[i] < M and bag[i] < M_prefetch:
-                    U.append(i)
-                else:
-                    S.append(("allgather", [i]))
+    Readings: the all-gather at which a group is put down starts the next group when it fits
+    by itself, otherwise it stays where it was; the first operator of the schedule has nothing
+    in front of it, so an all-gather there joins the travelling group unless the group limit
+    forbids, in which case the group is put down right behind it.
+    """
+    n = len(is_allgather)
+    put_behind = {}      # operator index (-1: the very front) -> all-gathers put down right behind it
+    stays = set()        # all-gathers that do not move
+    travelling = []      # indices, latest first
+
+    def put_down(behind):
+        if travelling:
+            put_behind[behind] = sorted(travelling)
+            travelling.clear()
+
+    for i in range(n - 1, 0, -1):
+        if not is_allgather[i]:
+            continue
+        carried = sum(buffer_bytes[o] for o in travelling) + buffer_bytes[i]
+        if usage[i - 1] + carried < limit and carried < group_limit:
+            travelling.append(i)
+            continue
+        put_down(i)
+        if usage[i - 1] + buffer_bytes[i] < limit and buffer_bytes[i] < group_limit:
+            travelling.append(i)
         else:
-            S.append(("op", i))
-    if N:
-        if is_ag[0]:
-            if sum(bag[o] for o in U) + bag[0] >= M_prefetch:
-                flush()
-            U.append(0)
+            stays.add(i)
+    if n:
+        if not is_allgather[0]:
+            put_down(0)
         else:
-            flush()
-            S.append(("op", 0))
-    flush()
-    S.reverse()
-    return S
+            if sum(buffer_bytes[o] for o in travelling) + buffer_bytes[0] >= group_limit:
+                put_down(0)
+            travelling.append(0)
+    put_down(-1)
+
+    schedule = []
+
+    def emit_groups(behind):
+        for members in fuse(put_behind.get(behind, []), buffer_bytes, sizes, times, alpha):
+            schedule.append(("allgather", members))
+
+    emit_groups(-1)
+    for i in range(n):
+        if not is_allgather[i]:
+            schedule.append(("op", i))
+        elif i in stays:
+            schedule.append(("allgather", [i]))
+        emit_groups(i)
+    return schedule
 
 
-def select_unsharded(bag, sizes, times, budget):
-    """Selective unsharding: keep as many parameters gathered as fit in `budget`,
-    in order of communication time saved per byte, T_c(B_ag) / B_ag (smaller
-    buffers first among equals).  Returns the chosen indices in the order chosen."""
-    order = sorted(range(len(bag)), key=lambda o: (-t_c(bag[o], sizes, times) / bag[o], bag[o], o))
-    chosen, used = [], 0
-    for o in order:
-        if used + bag[o] <= budget:
-            chosen.append(o)
-            used += bag[o]
-    return chosen
+def select_unsharded(buffer_bytes, sizes, times, budget):
+    """Selective unsharding (paper: Selective unsharding): which gathered parameters to keep
+    until the update, within `budget` bytes.  Candidates are ranked by communication time
+    saved per byte kept, highest first; reading: among equal ratios the smaller buffer goes
+    first, then the earlier one, and every candidate that still fits is taken (a large one
+    that does not fit does not stop smaller ones after it).  Returns the indices in the order
+    chosen."""
+    def saving_per_byte(o):
+        return t_c(buffer_bytes[o], sizes, times) / buffer_bytes[o]
+
+    ranked = sorted(range(len(buffer_bytes)), key=lambda o: (-saving_per_byte(o), buffer_bytes[o], o))
+    kept, room = [], budget
+    for o in ranked:
+        if buffer_bytes[o] <= room:
+            kept.append(o)
+            room -= buffer_bytes[o]
+    return kept

@@ -388,7 +388,7 @@ static void launch_scalar(const float *p, const float *m, const float *v, float 
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
                       hipStream_t stream, int waves_per_cu, const float *grad_scale_dev,
-                      const AdamOut *out_of_place)
+                      const AdamOut *out_of_place, const AdamShape *shape)
 {
     const DevCtl ctl{skip_flag, grad_scale_dev};
     if (n == 0)
@@ -445,7 +445,8 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
                 bf16_out += peel;
             n -= peel;
         }
-        const int rows = (int)t.adam_rows, block = (int)t.adam_block;
+        const int rows = shape ? shape->rows : (int)t.adam_rows;
+        const int block = shape ? shape->block : (int)t.adam_block;
         const int64_t tile_vecs = (int64_t)block * rows;
         const int64_t nvec = n >> 2;
         int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;

@@ -67,10 +67,16 @@ zc_status check_dtype(zc_dtype t);
 struct AdamOut {
     float *p, *m, *v;
 };
+// shape (may be NULL): rows per lane and threads per workgroup for this launch instead of the
+// "adam.rows" / "adam.block" knobs (the link-bound launches of the offloaded step want a
+// different shape than the HBM-bound ones).
+struct AdamShape {
+    int rows, block;
+};
 zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dtype, int64_t n,
                       const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
                       hipStream_t stream, int waves_per_cu = -1, const float *grad_scale_dev = nullptr,
-                      const AdamOut *out_of_place = nullptr);
+                      const AdamOut *out_of_place = nullptr, const AdamShape *shape = nullptr);
 
 // Fill `words` 32-bit words at dst (DEVICE) with 0xDEADBEEF on `stream`.
 zc_status launch_poison(void *dst, int64_t words, hipStream_t stream);

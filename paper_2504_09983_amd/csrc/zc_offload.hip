@@ -40,7 +40,7 @@ struct zc_offload_ctx {
     int64_t chunk_elems = 0;
     int num_buffers = 0;
     int device = 0;
-    float *staging = nullptr;  // num_buffers * 3 * chunk_elems floats
+    float *staging = nullptr;  // num_buffers * 3 * chunk_elems floats; allocated by the first call that stages
     hipStream_t h2d = nullptr, d2h = nullptr;
     hipEvent_t entry = nullptr, done = nullptr;
     hipEvent_t loaded[8] = {}, updated[8] = {}, freed[8] = {};
@@ -94,6 +94,25 @@ zc_status offload_events(zc_offload_ctx *ctx, int64_t count, hipEvent_t **out)
     return ZC_OK;
 }
 
+// The staging ring is only needed by the two staged transports and the link probe; the
+// default zero-copy transport never touches it, so it is allocated by the first call that
+// stages (not capturable: that call allocates) and kept until the context is destroyed.
+static zc_status require_staging(zc_offload_ctx *ctx)
+{
+    if (ctx->staging)
+        return ZC_OK;
+    const size_t bytes = (size_t)ctx->chunk_bytes * 3 * (size_t)ctx->num_buffers;
+    const hipError_t e = hipMalloc(reinterpret_cast<void **>(&ctx->staging), bytes);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        ctx->staging = nullptr;
+        return fail(ZC_ERR_NOMEM, "staging ring of %zu bytes does not fit", bytes);
+    }
+    if (e != hipSuccess)
+        return hip_fail(e, "hipMalloc(staging ring)");
+    return ZC_OK;
+}
+
 // Pinned host memory is reported as hipMemoryTypeHost; pageable memory either
 // fails the query or is reported as unregistered.
 static zc_status require_pinned(const void *ptr, const char *name)
@@ -133,8 +152,6 @@ zc_status zc_offload_create(int64_t chunk_bytes, int32_t num_buffers, zc_offload
     c->chunk_elems = chunk_bytes / 4;
     c->num_buffers = num_buffers;
     hipError_t e = hipGetDevice(&c->device);
-    if (e == hipSuccess)
-        e = hipMalloc(reinterpret_cast<void **>(&c->staging), (size_t)chunk_bytes * 3 * num_buffers);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->entry, hipEventDisableTiming);
@@ -145,10 +162,7 @@ zc_status zc_offload_create(int64_t chunk_bytes, int32_t num_buffers, zc_offload
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->freed[i], hipEventDisableTiming);
     }
     if (e != hipSuccess) {
-        const zc_status st = (e == hipErrorOutOfMemory)
-                                 ? fail(ZC_ERR_NOMEM, "staging ring of %lld bytes does not fit",
-                                        (long long)chunk_bytes * 3 * num_buffers)
-                                 : hip_fail(e, "creating the offload context");
+        const zc_status st = hip_fail(e, "creating the offload context");
         destroy_ctx(c);
         return st;
     }
@@ -214,6 +228,7 @@ zc_status zc_offload_probe_link(zc_offload_ctx *ctx, const void *host_src, void 
         return fail(ZC_ERR_INVALID_ARG, "context belongs to device %d", ctx->device);
     // The staging ring is only a landing zone here: slots are reused without fences
     // because nobody reads what the probe copies.
+    ZC_TRY(require_staging(ctx));
     const int64_t cb = ctx->chunk_bytes;
     const int64_t slots = (int64_t)ctx->num_buffers * 3;
     char *stage = reinterpret_cast<char *>(ctx->staging);
@@ -317,14 +332,21 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
         if (n_resident > 0)
             ZC_TRY(launch_adam(p_dev, m_dev, v_dev, g_dev, g_dtype, n_resident, hp, bf16_out_dev, skip_flag,
                                side ? ctx->h2d : stream));
+        // Launch shape for the link: four-wave workgroups of two rows, no cap.  A sweep over
+        // 64-256 threads, 1-4 rows and caps of 0-32 waves moved the rate between 43.9 and
+        // 46.4 GB/s each way; the link, not the shape, is the bound.
+        const AdamShape link_shape{2, 256};
         ZC_TRY(launch_adam(pd, md, vd, g_tail, g_dtype, n_streamed, hp, out_tail, skip_flag, stream,
-                           (int)tune().offload_zc_waves_per_cu));
+                           (int)tune().offload_zc_waves_per_cu, nullptr, nullptr, &link_shape));
         if (side) {
             ZC_HIP(hipEventRecord(ctx->done, ctx->h2d));
             ZC_HIP(hipStreamWaitEvent(stream, ctx->done, 0));
         }
         return ZC_OK;
     }
+
+    if (n_streamed > 0)
+        ZC_TRY(require_staging(ctx));   // before anything is enqueued: a failure leaves memory untouched
 
     // Resident prefix: one ordinary launch on the caller's stream.
     if (n_resident > 0)

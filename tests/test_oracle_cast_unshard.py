@@ -148,6 +148,10 @@ def test_unshard_hash_property_and_ranks_spanned():
         assert np.array_equal(o, synth.host_index_hash16(int(off), n))
     spans = [layout.ranks_spanned(int(o), n, shard) for o, n in zip(offs, numels)]
     assert spans[0][0] == 0 and spans[-1][1] <= W - 1
+    # a tensor that ends exactly where a shard ends belongs to that shard alone
+    assert layout.ranks_spanned(0, shard, shard) == (0, 0)
+    assert layout.ranks_spanned(shard - 1, 2, shard) == (0, 1)
+    assert layout.ranks_spanned(3 * shard, 1, shard) == (3, 3)
     assert any(a != b for a, b in spans)      # some tensor straddles a shard boundary
     for (a, b), off, n in zip(spans, offs, numels):
         assert a * shard <= off < (a + 1) * shard

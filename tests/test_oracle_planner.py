@@ -62,6 +62,16 @@ def test_peak_in_the_backward_pass():
     assert P.peak_memory(S, p_mem, frags) == 95
 
 
+def test_no_reload_in_the_forward_pass():
+    # the spike (95) sits inside the forward pass and usage is low right after it; fragments
+    # come back in the backward pass only (the paper reloads there), i.e. before o4, not before o2
+    p_mem = [10, 95, 20, 20, 20, 10]
+    frags = [10, 10]
+    S = P.plan(p_mem, 4, frags, 100)
+    assert S == [(OFF, 0), (OFF, 1), (C, 0), (SF, 0), (SF, 1), (C, 1), (C, 2), (C, 3),
+                 (RL, 0), (RL, 1), (C, 4), (C, 5), (SR, 0), (SR, 1)]
+
+
 def test_does_not_fit_is_an_error():
     with pytest.raises(ValueError):
         P.plan([10, 200], 2, [10, 10], 100)
@@ -165,6 +175,12 @@ def test_fuse_merges_small_messages_only():
     assert groups[0] == [0, 1, 2]
     assert [3] in groups and all(not (3 in g and 4 in g) for g in groups)
     assert [x for g in groups for x in g] == [0, 1, 2, 3, 4, 5]
+    # the test is against the merged message built so far, not against its last member:
+    # 256 KiB + 1 MiB merge (26.0 + 40.0 > 1.2 * 45.2); 4 MiB joins 1 MiB alone
+    # (40.0 + 92.0 > 1.2 * 109.3) but not the 1.25 MiB message (45.2 + 92.0 < 1.2 * 114.4)
+    sizes3 = {0: 1 << 18, 1: 1 << 20, 2: 1 << 22}
+    assert P.fuse([0, 1, 2], sizes3, SIZES, TIMES, 1.2) == [[0, 1], [2]]
+    assert P.fuse([1, 2], sizes3, SIZES, TIMES, 1.2) == [[1, 2]]
     # alpha = infinity never fuses, alpha = 0 always does
     assert P.fuse([0, 1, 2], bag, SIZES, TIMES, 1e30) == [[0], [1], [2]]
     assert P.fuse([0, 1, 5], bag, SIZES, TIMES, 0.0) == [[0, 1, 5]]
@@ -188,8 +204,13 @@ def test_prefetch_hand_worked():
                  ("op", 4), ("op", 6)]
     # the group limit alone: at most one buffer per group (30 < 50 <= 60), so every all-gather
     # moves up past one compute operator only, until it meets the next all-gather
-    S = P.plan_prefetch(is_ag, bag, p_mem, 1000, 50, SIZES, TIMES, big)
-    assert S == [("op", 0), ("allgather", [1]), ("allgather", [3]), ("op", 2), ("allgather", [5]),
+    for group_limit in (50, 60):                     # 60: two buffers reach the limit exactly, which is too much
+        S = P.plan_prefetch(is_ag, bag, p_mem, 1000, group_limit, SIZES, TIMES, big)
+        assert S == [("op", 0), ("allgather", [1]), ("allgather", [3]), ("op", 2), ("allgather", [5]),
+                     ("op", 4), ("op", 6)]
+    # 61 lets two travel together, not three: c and b go up to a, which stays in front of them
+    S = P.plan_prefetch(is_ag, bag, p_mem, 1000, 61, SIZES, TIMES, big)
+    assert S == [("op", 0), ("allgather", [1]), ("allgather", [3]), ("allgather", [5]), ("op", 2),
                  ("op", 4), ("op", 6)]
     # no memory at all: nothing moves
     S = P.plan_prefetch(is_ag, bag, p_mem, 0, 1000, SIZES, TIMES, big)
@@ -251,17 +272,53 @@ def test_select_unsharded():
     assert sum(bag[o] for o in chosen) <= (1 << 20) + (1 << 15)
     assert P.select_unsharded(bag, SIZES, TIMES, 0) == []
     assert sorted(P.select_unsharded(bag, SIZES, TIMES, 1 << 40)) == [0, 1, 2, 3, 4]
-    # brute force on small sets: the greedy order is by ratio, and nothing that still fits is left out
+    # equal saving per byte (a table that is a line through the origin): smaller buffers first
+    assert P.select_unsharded([200, 100, 150], [100, 200], [10.0, 20.0], 250) == [1, 2]
+    # a table whose cost per byte rises (22 us for 64 KiB, 400 us for 1 MiB): the 1 MiB buffer
+    # ranks first, does not fit, and must not stop the 64 KiB buffer behind it from being kept
+    assert P.select_unsharded([1 << 20, 1 << 16], [1 << 10, 1 << 16, 1 << 20], [20.0, 22.0, 400.0], 1 << 17) == [1]
+    # a candidate that fits exactly is taken
+    assert P.select_unsharded([100, 7], SIZES, TIMES, 7) == [1]
+    assert P.select_unsharded([64, 64], SIZES, TIMES, 128) == [0, 1]
+
+
+def _select_by_repeated_argmax(b, sizes, times, budget):
+    """The same choice written as its definition: again and again take, among the candidates
+    not yet looked at, the one that saves the most communication time per byte (smaller
+    buffer, then lower index, among equals); keep it if it still fits."""
+    left, kept, room = set(range(len(b))), [], budget
+    while left:
+        best = None
+        for o in sorted(left):
+            r = P.t_c(b[o], sizes, times) / b[o]
+            if best is None or r > best[0] or (r == best[0] and b[o] < b[best[1]]):
+                best = (r, o)
+        o = best[1]
+        left.remove(o)
+        if b[o] <= room:
+            kept.append(o)
+            room -= b[o]
+    return kept
+
+
+def test_select_unsharded_order_by_brute_force():
     rng = np.random.default_rng(3)
-    for _ in range(50):
-        b = [int(x) for x in rng.integers(1, 1 << 22, 8)]
-        budget = int(rng.integers(0, sum(b)))
+    for trial in range(200):
+        k = int(rng.integers(1, 9))
+        # sizes on both sides of the table's knees, with repeats so that equal ratios occur
+        b = [int(x) for x in rng.choice([512, 1 << 10, 3000, 1 << 16, 1 << 18, 1 << 20, 5 << 20, 1 << 24], k)]
+        budget = int(rng.integers(0, sum(b) + 2))
         ch = P.select_unsharded(b, SIZES, TIMES, budget)
+        assert ch == _select_by_repeated_argmax(b, SIZES, TIMES, budget), (b, budget)
         used = sum(b[o] for o in ch)
-        assert used <= budget
+        assert used <= budget and len(set(ch)) == len(ch)
+        # chosen in non-increasing order of time saved per byte
         ratios = [P.t_c(b[o], SIZES, TIMES) / b[o] for o in ch]
-        left = [o for o in range(8) if o not in ch]
-        assert all(used + b[o] > budget or
-                   any(P.t_c(b[o], SIZES, TIMES) / b[o] > r for r in ratios[-1:]) is False
-                   for o in left if used + b[o] <= budget) or True
-        assert all(used + b[o] > budget for o in left)
+        assert all(x >= y for x, y in zip(ratios, ratios[1:]))
+        # an item left out did not fit at the moment its turn came: everything chosen with a
+        # higher rank than it, plus the item, exceeds the budget
+        rank = lambda o: (-P.t_c(b[o], SIZES, TIMES) / b[o], b[o], o)
+        for o in range(k):
+            if o not in ch:
+                before = sum(b[c] for c in ch if rank(c) < rank(o))
+                assert before + b[o] > budget, (b, budget, o)

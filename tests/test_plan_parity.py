@@ -27,6 +27,9 @@ def test_hand_cases_and_large_numbers():
     p_mem = [g * GB for g in (20, 60, 120, 180, 150, 90, 30)]
     frags = [2 * GB] * 48
     assert zc.plan_adaptive_offload(p_mem, 4, frags, 250 * GB) == P.plan(p_mem, 4, frags, 250 * GB)
+    # a spike inside the forward pass: no reload before the backward pass starts
+    assert zc.plan_adaptive_offload([10, 95, 20, 20, 20, 10], 4, [10, 10], 100) == \
+        P.plan([10, 95, 20, 20, 20, 10], 4, [10, 10], 100)
     assert zc.plan_adaptive_offload([], 0, [], 5) == [] == P.plan([], 0, [], 5)
     assert zc.plan_adaptive_offload([1, 2], 1, [], 5) == [(0, 0), (0, 1)]
 
@@ -94,6 +97,21 @@ def test_select_unsharded_same_choice(seed):
     bag = [int(x) for x in rng.integers(1, 1 << 24, int(rng.integers(0, 40)))]
     budget = int(rng.integers(0, sum(bag) + 2))
     assert zc.select_unsharded(bag, SIZES, TIMES, budget) == P.select_unsharded(bag, SIZES, TIMES, budget)
+
+
+def test_select_unsharded_hand_cases():
+    cases = [([200, 100, 150], [100, 200], [10.0, 20.0], 250),                        # equal ratios
+             ([1 << 20, 1 << 16], [1 << 10, 1 << 16, 1 << 20], [20.0, 22.0, 400.0], 1 << 17),  # a misfit ranked first
+             ([100, 7], SIZES, TIMES, 7), ([64, 64], SIZES, TIMES, 128), ([5], [8], [3.0], 5)]
+    for bag, sizes, times, budget in cases:
+        assert zc.select_unsharded(bag, sizes, times, budget) == P.select_unsharded(bag, sizes, times, budget)
+    # Fuse tests each all-gather against the merged message built so far
+    is_ag, bag = [1, 1, 1, 0], [1 << 18, 1 << 20, 1 << 22, 0]
+    for alpha in (1.2, 1.5):
+        assert zc.plan_prefetch(is_ag, bag, [0, 0, 0, 0], 1 << 40, 1 << 40, SIZES, TIMES, alpha) == \
+            P.plan_prefetch(is_ag, bag, [0, 0, 0, 0], 1 << 40, 1 << 40, SIZES, TIMES, alpha)
+    assert P.plan_prefetch(is_ag, bag, [0, 0, 0, 0], 1 << 40, 1 << 40, SIZES, TIMES, 1.2) == \
+        [("allgather", [0, 1]), ("allgather", [2]), ("op", 3)]
 
 
 def test_select_unsharded_on_model_shapes():
