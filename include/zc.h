@@ -422,18 +422,24 @@ zc_status zc_grad_sqnorm_static(const void *g, zc_dtype g_dtype, int64_t n, floa
  *                      unused dynamic-LDS request; 0 = no cap; -1 (default) = 12 with
  *                      bf16 gradients, 11 with fp32 gradients, one more from 2^32
  *                      elements on
- *   "adam.nontemporal" 0 = ordinary loads and stores, 1 (default) = both non-temporal,
- *                      2 = loads only, 3 = stores only
+ *   "adam.nontemporal" 0 = ordinary loads and stores, 1 = both non-temporal, 2 = loads only,
+ *                      3 = stores only, 4 (default) = non-temporal loads and write-through
+ *                      streaming stores (buffer stores with the nt and sc1 bits)
  *   "adam.arith"       0 = fp32 only, 1 = fp64 multiply-adds with fp32 sqrt/div,
  *                      2 = fp64 throughout
  *   "copy.waves_per_cu", "cast.waves_per_cu", "accum.waves_per_cu"  the same cap for
- *                      unshard, the cast and gradient accumulation
- *   "copy.nontemporal"  non-temporal accesses in cast and unshard
+ *                      unshard (16), the cast (20) and gradient accumulation (24)
+ *   "reduce.unroll"    128-bit loads in flight per lane in zc_grad_sqnorm: 2, 4 or 8 (default)
+ *   "reduce.blocks_per_cu" persistent 256-thread workgroups per compute unit in
+ *                      zc_grad_sqnorm: 1-16, default 2
+ *   "copy.nontemporal"  cast, unshard, accumulation: 0 = ordinary accesses, 1 = non-temporal,
+ *                      2 (default) = non-temporal loads and write-through streaming stores
  *   "launch.max_grid"  workgroups per launch (default 2^30); larger jobs are cut into
  *                      several launches
  *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default),
  *                      2 = staged reads + kernel writes pinned host
  *   "offload.zc_waves_per_cu"  resident-wave cap of the zero-copy kernel (0 = none)
+ *   "offload.zc_block", "offload.zc_rows"  its threads per workgroup (256) and rows (2)
  *   "offload.max_ahead" 1 (default) = the staged ring blocks the host so that it never runs
  *                      more than num_buffers chunks ahead of finished copy-backs (deep copy
  *                      queues were measured to halve the link rate); 0 = enqueue everything

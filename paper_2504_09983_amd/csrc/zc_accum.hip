@@ -23,7 +23,9 @@ __device__ __forceinline__ float acc_elem(float a, float g, double scale)
 }
 
 // Requires acc 16-byte aligned and micro aligned to 4 elements.
-template <bool G_BF16>
+// STREAM: the sums are written with write-through streaming stores (stream_out_rsrc) instead
+// of plain non-temporal ones.
+template <bool G_BF16, bool STREAM>
 __global__ __launch_bounds__(kAccBlock) void accumulate_vec_kernel(float *__restrict__ acc,
                                                                    const void *__restrict__ micro,
                                                                    int64_t n, int64_t tile0, double scale)
@@ -49,6 +51,10 @@ __global__ __launch_bounds__(kAccBlock) void accumulate_vec_kernel(float *__rest
             }
         }
     }
+    const int64_t tile_first = tile * (kAccBlock * kAccRows);
+    int64_t room = nvec - tile_first;
+    room = room < 0 ? 0 : (room > kAccBlock * kAccRows ? kAccBlock * kAccRows : room);
+    const __amdgpu_buffer_rsrc_t ra = stream_out_rsrc(a4 + tile_first, room * 16);
 #pragma unroll
     for (int r = 0; r < kAccRows; ++r) {
         const int64_t i = first + r * kAccBlock;
@@ -57,7 +63,11 @@ __global__ __launch_bounds__(kAccBlock) void accumulate_vec_kernel(float *__rest
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 o[k] = acc_elem(av[r][k], gv[r][k], scale);
-            __builtin_nontemporal_store(o, a4 + i);
+            if constexpr (STREAM)
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(stream_u32x4, o), ra,
+                                                       (int)(threadIdx.x + r * kAccBlock) * 16, 0, kAuxStreamOut);
+            else
+                __builtin_nontemporal_store(o, a4 + i);
         }
     }
     const int64_t i = (nvec << 2) + threadIdx.x;
@@ -123,12 +133,18 @@ extern "C" zc_status zc_grad_accumulate(float *acc, const void *micro, zc_dtype 
         const int64_t kAccMaxGrid = tune().launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kAccMaxGrid) {
             const int64_t count = (ntiles - tile0) < kAccMaxGrid ? (ntiles - tile0) : kAccMaxGrid;
-            if (bf16)
-                hipLaunchKernelGGL(accumulate_vec_kernel<true>, dim3((unsigned)count), dim3(kAccBlock), lds,
-                                   stream, acc, micro, n, tile0, (double)scale);
-            else
-                hipLaunchKernelGGL(accumulate_vec_kernel<false>, dim3((unsigned)count), dim3(kAccBlock), lds,
-                                   stream, acc, micro, n, tile0, (double)scale);
+            const bool stream_out = tune().copy_nontemporal == 2;
+#define ZC_ACC(GB, ST)                                                                                  \
+    hipLaunchKernelGGL((accumulate_vec_kernel<GB, ST>), dim3((unsigned)count), dim3(kAccBlock), lds, stream, \
+                       acc, micro, n, tile0, (double)scale)
+            if (bf16) {
+                if (stream_out) ZC_ACC(true, true);
+                else ZC_ACC(true, false);
+            } else {
+                if (stream_out) ZC_ACC(false, true);
+                else ZC_ACC(false, false);
+            }
+#undef ZC_ACC
         }
     } else {
         int cus = 0;

@@ -157,7 +157,8 @@ __device__ __forceinline__ void st(T *ptr, T val)
         *ptr = val;
 }
 
-// NT: 0 = ordinary loads and stores, 1 = both non-temporal, 2 = loads only, 3 = stores only.
+// NT: 0 = ordinary loads and stores, 1 = both non-temporal, 2 = loads only, 3 = stores only,
+// 4 = non-temporal loads and write-through streaming stores (stream_out_rsrc, zc_internal.h).
 template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH, bool GUARD>
 __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, const f32x4 *v4,
                                           f32x4 *po4, f32x4 *mo4, f32x4 *vo4,
@@ -168,7 +169,21 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
     // used after the tile's loads have been issued, so their latency hides behind them.
     const int32_t skip_now = ctl.skip ? *ctl.skip : 0;
     const float dev_scale = ctl.gscale ? *ctl.gscale : 1.0f;
-    constexpr bool NTL = NT == 1 || NT == 2, NTS = NT == 1 || NT == 3;
+    constexpr bool NTL = NT == 1 || NT == 2 || NT == 4, NTS = NT == 1 || NT == 3;
+    // mode 4: one descriptor per output array over this workgroup's tile (uniform values)
+    typedef stream_u32x4 u32x4v;
+    typedef stream_u32x2 u32x2v;
+    constexpr int64_t kTileVecs = (int64_t)BLOCK * ROWS;
+    const int64_t tile_first = first - threadIdx.x;
+    __amdgpu_buffer_rsrc_t rp, rm, rv, ro;
+    if constexpr (NT == 4) {
+        int64_t vecs = nvec - tile_first;            // whole 16-byte vectors this tile may write
+        vecs = vecs < 0 ? 0 : (vecs > kTileVecs ? kTileVecs : vecs);
+        rp = stream_out_rsrc(po4 + tile_first, vecs * 16);
+        rm = stream_out_rsrc(mo4 + tile_first, vecs * 16);
+        rv = stream_out_rsrc(vo4 + tile_first, vecs * 16);
+        ro = stream_out_rsrc(out2 ? (void *)(out2 + tile_first) : (void *)po4, out2 ? vecs * 8 : 0);
+    }
     f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -207,14 +222,27 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
                 mv[r][k] = me;
                 vv[r][k] = ve;
             }
-            st<NTS>(po4 + i, pv[r]);
-            st<NTS>(mo4 + i, mv[r]);
-            st<NTS>(vo4 + i, vv[r]);
-            if (out2) {
-                u32x2 w;
-                w.x = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
-                w.y = bf16_rne(pv[r].z) | (bf16_rne(pv[r].w) << 16);
-                st<NTS>(out2 + i, w);
+            if constexpr (NT == 4) {
+                const int voff = (int)(threadIdx.x + r * BLOCK) * 16;
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, pv[r]), rp, voff, 0, kAuxStreamOut);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, mv[r]), rm, voff, 0, kAuxStreamOut);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, vv[r]), rv, voff, 0, kAuxStreamOut);
+                if (out2) {
+                    u32x2v w;
+                    w[0] = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
+                    w[1] = bf16_rne(pv[r].z) | (bf16_rne(pv[r].w) << 16);
+                    __builtin_amdgcn_raw_buffer_store_b64(w, ro, voff >> 1, 0, kAuxStreamOut);
+                }
+            } else {
+                st<NTS>(po4 + i, pv[r]);
+                st<NTS>(mo4 + i, mv[r]);
+                st<NTS>(vo4 + i, vv[r]);
+                if (out2) {
+                    u32x2 w;
+                    w.x = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
+                    w.y = bf16_rne(pv[r].z) | (bf16_rne(pv[r].w) << 16);
+                    st<NTS>(out2 + i, w);
+                }
             }
         }
     }
@@ -342,7 +370,8 @@ static void pick_nt(int nt, int arith, const VecLaunch &a)
     if (nt == 0) pick_arith<ROWS, BLOCK, G_BF16, 0>(arith, a);
     else if (nt == 1) pick_arith<ROWS, BLOCK, G_BF16, 1>(arith, a);
     else if (nt == 2) pick_arith<ROWS, BLOCK, G_BF16, 2>(arith, a);
-    else pick_arith<ROWS, BLOCK, G_BF16, 3>(arith, a);
+    else if (nt == 3) pick_arith<ROWS, BLOCK, G_BF16, 3>(arith, a);
+    else pick_arith<ROWS, BLOCK, G_BF16, 4>(arith, a);
 }
 
 template <int ROWS, int BLOCK>
@@ -447,6 +476,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
         }
         const int rows = shape ? shape->rows : (int)t.adam_rows;
         const int block = shape ? shape->block : (int)t.adam_block;
+        const int nt = shape ? shape->nontemporal : (int)t.adam_nontemporal;
         const int64_t tile_vecs = (int64_t)block * rows;
         const int64_t nvec = n >> 2;
         int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
@@ -469,9 +499,9 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             a.grid = dim3((unsigned)count);
             a.tile0 = tile0;
-            if (block == 64) pick_rows<64>(rows, g_bf16, (int)t.adam_nontemporal, arith, a);
-            else if (block == 128) pick_rows<128>(rows, g_bf16, (int)t.adam_nontemporal, arith, a);
-            else pick_rows<256>(rows, g_bf16, (int)t.adam_nontemporal, arith, a);
+            if (block == 64) pick_rows<64>(rows, g_bf16, nt, arith, a);
+            else if (block == 128) pick_rows<128>(rows, g_bf16, nt, arith, a);
+            else pick_rows<256>(rows, g_bf16, nt, arith, a);
         }
     }
     ZC_HIP(hipGetLastError());

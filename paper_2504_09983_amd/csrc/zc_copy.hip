@@ -49,7 +49,9 @@ constexpr int kCastRows = 4;    // 4 x 256 elements per workgroup tile
 
 // Requires src 16-byte and dst 8-byte aligned.  One tile per workgroup; `tile0`
 // is the tile of workgroup 0 (launches are cut to keep the grid below 2^31).
-template <bool NT>
+// NT: 0 = ordinary accesses, 1 = non-temporal loads and stores, 2 = non-temporal loads and
+// write-through streaming stores (stream_out_rsrc).
+template <int NT>
 __global__ __launch_bounds__(kCopyBlock) void cast_vec_kernel(const float *__restrict__ src,
                                                               uint16_t *__restrict__ dst, int64_t n,
                                                               int64_t tile0)
@@ -64,8 +66,12 @@ __global__ __launch_bounds__(kCopyBlock) void cast_vec_kernel(const float *__res
     for (int r = 0; r < kCastRows; ++r) {
         const int64_t i = first + r * kCopyBlock;
         if (i < nvec)
-            x[r] = ldc<NT>(s4 + i);
+            x[r] = ldc<(NT != 0)>(s4 + i);
     }
+    const int64_t tile_first = tile * (kCopyBlock * kCastRows);
+    int64_t room = nvec - tile_first;
+    room = room < 0 ? 0 : (room > kCopyBlock * kCastRows ? kCopyBlock * kCastRows : room);
+    const __amdgpu_buffer_rsrc_t rd = stream_out_rsrc(d2 + tile_first, room * 8);
 #pragma unroll
     for (int r = 0; r < kCastRows; ++r) {
         const int64_t i = first + r * kCopyBlock;
@@ -73,7 +79,14 @@ __global__ __launch_bounds__(kCopyBlock) void cast_vec_kernel(const float *__res
             u32x2 w;
             w.x = cast_rne(x[r].x) | (cast_rne(x[r].y) << 16);
             w.y = cast_rne(x[r].z) | (cast_rne(x[r].w) << 16);
-            stc<NT>(d2 + i, w);
+            if constexpr (NT == 2) {
+                stream_u32x2 o;
+                o[0] = w.x;
+                o[1] = w.y;
+                __builtin_amdgcn_raw_buffer_store_b64(o, rd, (int)(threadIdx.x + r * kCopyBlock) * 8, 0, kAuxStreamOut);
+            } else {
+                stc<(NT != 0)>(d2 + i, w);
+            }
         }
     }
     const int64_t i = (nvec << 2) + threadIdx.x;
@@ -137,7 +150,7 @@ __device__ __forceinline__ u32x4 load_src_vec(const uint16_t *s)
 // loads of a tile issue back to back (with the class tested per load the compiler waited
 // after each of them).  The per-vector bounds test stays on full tiles as well: a variant
 // without it measured 2.7 % slower.
-template <int ALIGN, bool NT>
+template <int ALIGN, int NT>
 __device__ __forceinline__ void copy_tile(const uint16_t *sb, u32x4 *db, int64_t t, int64_t body_vecs)
 {
     const int64_t first = t * kTileVecs + threadIdx.x;
@@ -146,13 +159,26 @@ __device__ __forceinline__ void copy_tile(const uint16_t *sb, u32x4 *db, int64_t
     for (int k = 0; k < kUnroll; ++k) {
         const int64_t i = first + k * kCopyBlock;
         if (i < body_vecs)
-            w[k] = load_src_vec<ALIGN, NT>(sb + (i << 3));
+            w[k] = load_src_vec<ALIGN, (NT != 0)>(sb + (i << 3));
     }
+    int64_t room = body_vecs - t * kTileVecs;      // uniform: the segment and its tile are per workgroup
+    room = room < 0 ? 0 : (room > kTileVecs ? kTileVecs : room);
+    const __amdgpu_buffer_rsrc_t rd = stream_out_rsrc(db + t * kTileVecs, room * 16);
 #pragma unroll
     for (int k = 0; k < kUnroll; ++k) {
         const int64_t i = first + k * kCopyBlock;
-        if (i < body_vecs)
-            stc<NT>(db + i, w[k]);
+        if (i < body_vecs) {
+            if constexpr (NT == 2) {
+                stream_u32x4 o;
+                o[0] = w[k].x;
+                o[1] = w[k].y;
+                o[2] = w[k].z;
+                o[3] = w[k].w;
+                __builtin_amdgcn_raw_buffer_store_b128(o, rd, (int)(threadIdx.x + k * kCopyBlock) * 16, 0, kAuxStreamOut);
+            } else {
+                stc<(NT != 0)>(db + i, w[k]);
+            }
+        }
     }
 }
 
@@ -161,7 +187,7 @@ constexpr int kHintShift = 10;  // one hint per 1024 tiles
 // `hint[k]` is the segment that owns tile k << kHintShift, so the search for a
 // tile's segment starts in a range that is almost always a single segment: one
 // dependent load instead of log2(nsegs) of them before the wave can issue its copy.
-template <bool NT>
+template <int NT>
 __global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const uint16_t *__restrict__ gathered,
                                                              const SegDesc *__restrict__ segs,
                                                              const int32_t *__restrict__ hint,
@@ -260,11 +286,14 @@ zc_status zc_cast_bf16(const float *src, uint16_t *dst, int64_t n, void *hip_str
         const int64_t kMaxGrid = t.launch_max_grid;
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
-            if (t.copy_nontemporal)
-                hipLaunchKernelGGL(cast_vec_kernel<true>, dim3((unsigned)count), dim3(kCopyBlock), lds,
+            if (t.copy_nontemporal == 2)
+                hipLaunchKernelGGL(cast_vec_kernel<2>, dim3((unsigned)count), dim3(kCopyBlock), lds,
+                                   stream, src, dst, n, tile0);
+            else if (t.copy_nontemporal == 1)
+                hipLaunchKernelGGL(cast_vec_kernel<1>, dim3((unsigned)count), dim3(kCopyBlock), lds,
                                    stream, src, dst, n, tile0);
             else
-                hipLaunchKernelGGL(cast_vec_kernel<false>, dim3((unsigned)count), dim3(kCopyBlock), lds,
+                hipLaunchKernelGGL(cast_vec_kernel<0>, dim3((unsigned)count), dim3(kCopyBlock), lds,
                                    stream, src, dst, n, tile0);
         }
     } else {
@@ -400,11 +429,14 @@ zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void
     for (int64_t tile0 = 0; tile0 < plan->ntiles; tile0 += kMaxGrid) {
         const int64_t left = plan->ntiles - tile0;
         const int64_t count = left < kMaxGrid ? left : kMaxGrid;
-        if (t.copy_nontemporal)
-            hipLaunchKernelGGL(unshard_kernel<true>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
+        if (t.copy_nontemporal == 2)
+            hipLaunchKernelGGL(unshard_kernel<2>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
+                               gathered, plan->segs_dev, plan->hint_dev, plan->nsegs, tile0);
+        else if (t.copy_nontemporal == 1)
+            hipLaunchKernelGGL(unshard_kernel<1>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
                                gathered, plan->segs_dev, plan->hint_dev, plan->nsegs, tile0);
         else
-            hipLaunchKernelGGL(unshard_kernel<false>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
+            hipLaunchKernelGGL(unshard_kernel<0>, dim3((unsigned)count), dim3(kCopyBlock), lds, stream,
                                gathered, plan->segs_dev, plan->hint_dev, plan->nsegs, tile0);
     }
     ZC_HIP(hipGetLastError());

@@ -131,15 +131,19 @@ static const Knob kKnobs[] = {
     {"adam.rows", &Tune::adam_rows, 1, 4},
     {"adam.block", &Tune::adam_block, 64, 256},
     {"adam.waves_per_cu", &Tune::adam_waves_per_cu, -1, 64},
-    {"adam.nontemporal", &Tune::adam_nontemporal, 0, 3},
+    {"adam.nontemporal", &Tune::adam_nontemporal, 0, 4},
     {"adam.arith", &Tune::adam_arith, 0, 2},
+    {"reduce.unroll", &Tune::reduce_unroll, 2, 8},
+    {"reduce.blocks_per_cu", &Tune::reduce_blocks_per_cu, 1, 16},
     {"copy.waves_per_cu", &Tune::copy_waves_per_cu, 0, 64},
     {"cast.waves_per_cu", &Tune::cast_waves_per_cu, 0, 64},
     {"accum.waves_per_cu", &Tune::accum_waves_per_cu, 0, 64},
-    {"copy.nontemporal", &Tune::copy_nontemporal, 0, 1},
+    {"copy.nontemporal", &Tune::copy_nontemporal, 0, 2},
     {"launch.max_grid", &Tune::launch_max_grid, 1, int64_t(1) << 30},
     {"offload.zero_copy", &Tune::offload_zero_copy, 0, 2},
     {"offload.zc_waves_per_cu", &Tune::offload_zc_waves_per_cu, 0, 64},
+    {"offload.zc_block", &Tune::offload_zc_block, 64, 256},
+    {"offload.zc_rows", &Tune::offload_zc_rows, 1, 4},
     {"offload.max_ahead", &Tune::offload_max_ahead, 0, 1},
     {"offload.d2h_on_compute", &Tune::offload_d2h_on_compute, 0, 1},
     {"offload.poison", &Tune::offload_poison, 0, 1},
@@ -171,7 +175,9 @@ zc_status zc_tune_set(const char *key, int64_t value)
         return zc::fail(ZC_ERR_INVALID_ARG, "unknown tuning key '%s'", key ? key : "(null)");
     const bool pow2 = value > 0 && (value & (value - 1)) == 0;
     if (value < k->lo || value > k->hi ||
-        ((k->field == &zc::Tune::adam_rows || k->field == &zc::Tune::adam_block) && !pow2))
+        ((k->field == &zc::Tune::adam_rows || k->field == &zc::Tune::adam_block ||
+          k->field == &zc::Tune::reduce_unroll || k->field == &zc::Tune::offload_zc_block ||
+          k->field == &zc::Tune::offload_zc_rows) && !pow2))
         return zc::fail(ZC_ERR_INVALID_ARG, "value %lld out of range for '%s'", (long long)value, key);
     zc::tune().*(k->field) = value;
     return ZC_OK;

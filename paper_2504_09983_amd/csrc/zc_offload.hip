@@ -332,10 +332,14 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
         if (n_resident > 0)
             ZC_TRY(launch_adam(p_dev, m_dev, v_dev, g_dev, g_dtype, n_resident, hp, bf16_out_dev, skip_flag,
                                side ? ctx->h2d : stream));
-        // Launch shape for the link: four-wave workgroups of two rows, no cap.  A sweep over
+        // Launch shape for the link (knobs offload.zc_block / zc_rows / zc_waves_per_cu):
+        // four-wave workgroups of two rows, no cap.  A sweep over
         // 64-256 threads, 1-4 rows and caps of 0-32 waves moved the rate between 43.9 and
         // 46.4 GB/s each way; the link, not the shape, is the bound.
-        const AdamShape link_shape{2, 256};
+        // Stores to host memory leave the chip whatever their cache policy; plain non-temporal
+        // ones measured 1 % faster over the link than the write-through form used in HBM.
+        const int link_nt = tune().adam_nontemporal == 4 ? 1 : (int)tune().adam_nontemporal;
+        const AdamShape link_shape{(int)tune().offload_zc_rows, (int)tune().offload_zc_block, link_nt};
         ZC_TRY(launch_adam(pd, md, vd, g_tail, g_dtype, n_streamed, hp, out_tail, skip_flag, stream,
                            (int)tune().offload_zc_waves_per_cu, nullptr, nullptr, &link_shape));
         if (side) {

@@ -63,10 +63,14 @@ __device__ __forceinline__ void block_fold(double sum, uint32_t bad, Partial *ou
     }
 }
 
-constexpr int kReduceUnroll = 4;  // 128-bit loads in flight per lane
 
-// bf16 input, 8 elements (16 bytes) per lane per load, kReduceUnroll loads issued
-// back to back.  Requires 16-byte alignment.
+constexpr int kFoldLoads = 4;  // loads whose squares are summed in fp32 before going to double
+
+// bf16 input, 8 elements (16 bytes) per lane per load, UNROLL loads issued back to back.
+// Requires 16-byte alignment.  fp32 sums run over the squares of at most kFoldLoads loads
+// (8 terms in each of four accumulators) and are folded into the lane's double sum from
+// there, so the result stays within an fp32 rounding of the exact sum whatever UNROLL is.
+template <int UNROLL>
 __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__restrict__ g, int64_t n,
                                                           Partial *__restrict__ partials)
 {
@@ -74,51 +78,52 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
     const u32x4 *g4 = reinterpret_cast<const u32x4 *>(g);
     double sum = 0.0;
     uint32_t worst = 0;  // running max of |bits| per half-word; >= 0x7F80 means Inf/NaN
-    const int64_t tile_vecs = 256 * kReduceUnroll;
+    const int64_t tile_vecs = 256 * UNROLL;
     const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t first = tile * tile_vecs + threadIdx.x;
-        // fp32 sums only within one tile (8 terms each), folded into the lane's double sum
-        // once per tile: the result stays within an fp32 rounding of the exact sum.
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        u32x4 w[kReduceUnroll];
+        u32x4 w[UNROLL];
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u) {
+        for (int u = 0; u < UNROLL; ++u) {
             const int64_t i = first + u * 256;
             w[u] = i < nvec ? __builtin_nontemporal_load(g4 + i) : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u) {
-            const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
-            float lo[4], hi[4];
+        for (int q = 0; q < UNROLL; q += kFoldLoads) {
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                lo[k] = __uint_as_float(ws[k] << 16);
-                hi[k] = __uint_as_float(ws[k] & 0xFFFF0000u);
-            }
-            a0 = fmaf(lo[0], lo[0], a0);
-            a1 = fmaf(hi[0], hi[0], a1);
-            a2 = fmaf(lo[1], lo[1], a2);
-            a3 = fmaf(hi[1], hi[1], a3);
-            a0 = fmaf(lo[2], lo[2], a0);
-            a1 = fmaf(hi[2], hi[2], a1);
-            a2 = fmaf(lo[3], lo[3], a2);
-            a3 = fmaf(hi[3], hi[3], a3);
-        }
-        const float tile_sum = (a0 + a1) + (a2 + a3);
-        // A NaN or Inf element makes its tile's fp32 sum non-finite; so does the square of a
-        // finite value above 1.8e19, which must not raise the flag.  Only such a tile looks
-        // at its elements one by one (they are still in registers).
-        if (!(fabsf(tile_sum) <= 3.4028234e38f)) {
-#pragma unroll
-            for (int u = 0; u < kReduceUnroll; ++u) {
+            for (int u = q; u < q + kFoldLoads && u < UNROLL; ++u) {
                 const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+                float lo[4], hi[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    worst = max(worst, max(ws[k] & 0x7FFFu, (ws[k] >> 16) & 0x7FFFu));
+                for (int k = 0; k < 4; ++k) {
+                    lo[k] = __uint_as_float(ws[k] << 16);
+                    hi[k] = __uint_as_float(ws[k] & 0xFFFF0000u);
+                }
+                a0 = fmaf(lo[0], lo[0], a0);
+                a1 = fmaf(hi[0], hi[0], a1);
+                a2 = fmaf(lo[1], lo[1], a2);
+                a3 = fmaf(hi[1], hi[1], a3);
+                a0 = fmaf(lo[2], lo[2], a0);
+                a1 = fmaf(hi[2], hi[2], a1);
+                a2 = fmaf(lo[3], lo[3], a2);
+                a3 = fmaf(hi[3], hi[3], a3);
             }
+            const float group_sum = (a0 + a1) + (a2 + a3);
+            // A NaN or Inf element makes its group's fp32 sum non-finite; so does the square of
+            // a finite value above 1.8e19, which must not raise the flag.  Only such a group
+            // looks at its elements one by one (they are still in registers).
+            if (!(fabsf(group_sum) <= 3.4028234e38f)) {
+#pragma unroll
+                for (int u = q; u < q + kFoldLoads && u < UNROLL; ++u) {
+                    const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        worst = max(worst, max(ws[k] & 0x7FFFu, (ws[k] >> 16) & 0x7FFFu));
+                }
+            }
+            sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
         }
-        sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     }
     // The last n % 8 elements, one lane each, in workgroup 0.
     const int64_t t = (nvec << 3) + threadIdx.x;
@@ -131,7 +136,9 @@ __global__ __launch_bounds__(256) void sqnorm_bf16_kernel(const uint16_t *__rest
     block_fold(sum, worst >= 0x7F80u ? 1u : 0u, partials + blockIdx.x);
 }
 
-// fp32 input, 4 elements per lane per load.  Requires 16-byte alignment.
+// fp32 input, 4 elements per lane per load (4 terms in each accumulator per group).
+// Requires 16-byte alignment.
+template <int UNROLL>
 __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict__ g, int64_t n,
                                                          Partial *__restrict__ partials)
 {
@@ -139,34 +146,37 @@ __global__ __launch_bounds__(256) void sqnorm_f32_kernel(const float *__restrict
     const f32x4 *g4 = reinterpret_cast<const f32x4 *>(g);
     double sum = 0.0;
     uint32_t worst = 0;
-    const int64_t tile_vecs = 256 * kReduceUnroll;
+    const int64_t tile_vecs = 256 * UNROLL;
     const int64_t ntiles = (nvec + tile_vecs - 1) / tile_vecs;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t first = tile * tile_vecs + threadIdx.x;
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;   // 4 terms each, then into the double sum
-        f32x4 x[kReduceUnroll];
+        f32x4 x[UNROLL];
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u) {
+        for (int u = 0; u < UNROLL; ++u) {
             const int64_t i = first + u * 256;
             x[u] = i < nvec ? __builtin_nontemporal_load(g4 + i) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u) {
-            a0 = fmaf(x[u].x, x[u].x, a0);
-            a1 = fmaf(x[u].y, x[u].y, a1);
-            a2 = fmaf(x[u].z, x[u].z, a2);
-            a3 = fmaf(x[u].w, x[u].w, a3);
-        }
-        const float tile_sum = (a0 + a1) + (a2 + a3);
-        if (!(fabsf(tile_sum) <= 3.4028234e38f)) {   // see the bf16 kernel: only then look closer
+        for (int q = 0; q < UNROLL; q += kFoldLoads) {
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
-            for (int u = 0; u < kReduceUnroll; ++u)
-                worst = max(max(worst, __float_as_uint(x[u].x) & 0x7FFFFFFFu),
-                            max(__float_as_uint(x[u].y) & 0x7FFFFFFFu,
-                                max(__float_as_uint(x[u].z) & 0x7FFFFFFFu,
-                                    __float_as_uint(x[u].w) & 0x7FFFFFFFu)));
+            for (int u = q; u < q + kFoldLoads && u < UNROLL; ++u) {
+                a0 = fmaf(x[u].x, x[u].x, a0);
+                a1 = fmaf(x[u].y, x[u].y, a1);
+                a2 = fmaf(x[u].z, x[u].z, a2);
+                a3 = fmaf(x[u].w, x[u].w, a3);
+            }
+            const float group_sum = (a0 + a1) + (a2 + a3);
+            if (!(fabsf(group_sum) <= 3.4028234e38f)) {   // see the bf16 kernel: only then look closer
+#pragma unroll
+                for (int u = q; u < q + kFoldLoads && u < UNROLL; ++u)
+                    worst = max(max(worst, __float_as_uint(x[u].x) & 0x7FFFFFFFu),
+                                max(__float_as_uint(x[u].y) & 0x7FFFFFFFu,
+                                    max(__float_as_uint(x[u].z) & 0x7FFFFFFFu,
+                                        __float_as_uint(x[u].w) & 0x7FFFFFFFu)));
+            }
+            sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
         }
-        sum += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
     }
     const int64_t t = (nvec << 2) + threadIdx.x;
     if (blockIdx.x == 0 && threadIdx.x < 4 && t < n) {
@@ -285,19 +295,29 @@ static zc_status enqueue_sqnorm(const void *g, bool bf16, int64_t n, float *sqno
     ZC_TRY(num_cus(&cus));
     int blocks = 0;
     if (n > 0) {
-        const int64_t per_lane = (bf16 ? 8 : 4) * kReduceUnroll;
+        const Tune &t = tune();
+        const int unroll = (int)t.reduce_unroll;      // 128-bit loads in flight per lane
+        const int64_t per_lane = (bf16 ? 8 : 4) * unroll;
         const int64_t want = (n / per_lane + 255) / 256;
-        int64_t cap = (int64_t)cus * 8;
+        int64_t cap = (int64_t)cus * t.reduce_blocks_per_cu;
         if (cap > kMaxPartials)
             cap = kMaxPartials;
         blocks = (int)(want < 1 ? 1 : (want > cap ? cap : want));
         if (aligned_to(g, 16)) {
+#define ZC_SQNORM(KERNEL, TYPE)                                                                          \
+    do {                                                                                                 \
+        if (unroll == 2)                                                                                 \
+            hipLaunchKernelGGL(KERNEL<2>, dim3(blocks), dim3(256), 0, stream, static_cast<const TYPE *>(g), n, partials); \
+        else if (unroll == 8)                                                                            \
+            hipLaunchKernelGGL(KERNEL<8>, dim3(blocks), dim3(256), 0, stream, static_cast<const TYPE *>(g), n, partials); \
+        else                                                                                             \
+            hipLaunchKernelGGL(KERNEL<4>, dim3(blocks), dim3(256), 0, stream, static_cast<const TYPE *>(g), n, partials); \
+    } while (0)
             if (bf16)
-                hipLaunchKernelGGL(sqnorm_bf16_kernel, dim3(blocks), dim3(256), 0, stream,
-                                   static_cast<const uint16_t *>(g), n, partials);
+                ZC_SQNORM(sqnorm_bf16_kernel, uint16_t);
             else
-                hipLaunchKernelGGL(sqnorm_f32_kernel, dim3(blocks), dim3(256), 0, stream,
-                                   static_cast<const float *>(g), n, partials);
+                ZC_SQNORM(sqnorm_f32_kernel, float);
+#undef ZC_SQNORM
         } else {
             if (bf16)
                 hipLaunchKernelGGL(sqnorm_scalar_kernel<true>, dim3(blocks), dim3(256), 0, stream, g, n,

@@ -155,7 +155,7 @@ def test_every_kernel_variant(arith, rows):
     keys = ("adam.arith", "adam.rows", "adam.nontemporal", "adam.block", "adam.waves_per_cu")
     old = {k: zc.tune_get(k) for k in keys}
     try:
-        for nt in (0, 1):
+        for nt in (0, 1, 2, 3, 4):
             for block, waves in ((64, 9), (128, 0), (256, 12)):
                 for k, val in zip(keys, (arith, rows, nt, block, waves)):
                     zc.tune_set(k, val)

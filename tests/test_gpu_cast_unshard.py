@@ -161,7 +161,7 @@ def test_unshard_every_relative_alignment(src_shift):
 
 def test_unshard_occupancy_cap_and_nontemporal():
     numels = [4096 * 64 + 3, 1000, 4096 * 200, 17]
-    for tune in ({"copy.waves_per_cu": 0}, {"copy.nontemporal": 0},
+    for tune in ({"copy.waves_per_cu": 0}, {"copy.nontemporal": 0}, {"copy.nontemporal": 2},
                  {"copy.waves_per_cu": 4, "copy.nontemporal": 1}):
         run_unshard(numels, tune=tune)
 
