@@ -216,7 +216,7 @@ def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, wit
 def placement_leg(torch, synth, zc, dev):
     """Where the caller puts p, m, v matters for small partitions: the same launch over the
     Llama-3-8B shard with the five arrays back to back (what an allocator gives for 4 GB arrays)
-    and with each array 36 GiB after the previous one inside one arena."""
+    and with each array 16 or 36 GiB after the previous one inside one arena."""
     n = 1_003_782_656
     arena = torch.empty(4 * 36 * GIB + 3 * GIB, dtype=torch.uint8, device=dev)
     base = arena.data_ptr()
@@ -232,6 +232,7 @@ def placement_leg(torch, synth, zc, dev):
 
     s0 = up(4 * n, 2 << 20)
     layouts = {"back_to_back": [0, s0, 2 * s0, 3 * s0, 3 * s0 + up(2 * n, 2 << 20)],
+               "16_GiB_apart": [k * 16 * GIB for k in range(5)],
                "36_GiB_apart": [k * 36 * GIB for k in range(5)]}
     out = {}
     for name, offs in layouts.items():

@@ -419,9 +419,8 @@ zc_status zc_grad_sqnorm_static(const void *g, zc_dtype g_dtype, int64_t n, floa
  *   "adam.rows"        128-bit vectors per lane per tile: 1 (default), 2 or 4
  *   "adam.block"       threads per workgroup: 64 (default), 128 or 256
  *   "adam.waves_per_cu" cap on resident waves per compute unit, enforced through an
- *                      unused dynamic-LDS request; 0 = no cap; -1 (default) = 12 with
- *                      bf16 gradients, 11 with fp32 gradients, one more from 2^32
- *                      elements on
+ *                      unused dynamic-LDS request; 0 = no cap; -1 (default) = 13 with
+ *                      bf16 gradients, 12 with fp32 gradients
  *   "adam.nontemporal" 0 = ordinary loads and stores, 1 = both non-temporal, 2 = loads only,
  *                      3 = stores only, 4 (default) = non-temporal loads and write-through
  *                      streaming stores (buffer stores with the nt and sc1 bits)

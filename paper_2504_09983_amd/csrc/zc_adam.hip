@@ -484,14 +484,13 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
         // Resident-wave cap: the caller's, else the knob's, else (knob at -1) what measured
-        // best on N(0, sigma) data with one-wave workgroups of one row: 12 waves per CU with
-        // bf16 gradients, 11 with fp32 gradients (one more 16-byte load per lane in flight),
-        // and one wave more for partitions of 2^32 elements and beyond.  Below the optimum
-        // the kernel is latency-bound, above it the eight read and write streams start to
-        // evict each other's open DRAM pages.
+        // best on N(0, sigma) data with one-wave workgroups of one row at all three model
+        // sizes: 13 waves per CU with bf16 gradients, 12 with fp32 gradients (one more
+        // 16-byte load per lane in flight).  Below the optimum the kernel is latency-bound,
+        // above it the eight read and write streams start to evict each other's open DRAM pages.
         int cap = waves_per_cu >= 0 ? waves_per_cu : (int)t.adam_waves_per_cu;
         if (cap < 0)
-            cap = (g_bf16 ? 12 : 11) + (n >= (int64_t(1) << 32) ? 1 : 0);
+            cap = g_bf16 ? 13 : 12;
         ZC_TRY(occupancy_cap_lds(cap, block, &lds));
         VecLaunch a{dim3(1), lds, stream, p, m, v, po, mo, vo, g, bf16_out, n, 0, s, ctl};
         const int64_t kMaxGrid = t.launch_max_grid;

@@ -75,10 +75,11 @@ def sweep_adam(args):
     for _, fn in variants.values():
         fn()
     torch.cuda.synchronize()
+    nt0 = zc.tune_get("adam.nontemporal")          # coarse and fine grids keep the library's access mode
     if args.grid == "coarse":
-        grid = [(b, r, w, 1) for b in (64, 128, 256) for r in (1, 2, 4) for w in (4, 6, 8, 9, 10, 11, 12, 14, 16, 20)]
+        grid = [(b, r, w, nt0) for b in (64, 128, 256) for r in (1, 2, 4) for w in (4, 6, 8, 9, 10, 11, 12, 14, 16, 20)]
     elif args.grid == "fine":
-        grid = [(64, r, w, 1) for r in (1, 2) for w in range(10, 17)] + [(128, 2, w, 1) for w in (12, 14, 16)]
+        grid = [(64, r, w, nt0) for r in (1, 2) for w in range(10, 17)] + [(128, 2, w, nt0) for w in (12, 14, 16)]
     else:
         grid = [(b, r, w, nt) for (b, r) in ((64, 1), (64, 2), (128, 2)) for w in (10, 12, 14, 16) for nt in (0, 1, 2, 3, 4)]
     print(f"# adam {args.workload} n={n} reps={reps}; columns: fraction of 8 TB/s per variant", flush=True)

@@ -169,6 +169,27 @@ def test_every_kernel_variant(arith, rows):
             zc.tune_set(k, val)
 
 
+@pytest.mark.parametrize("g_bf16", [True, False])
+def test_measured_error_of_each_arithmetic_variant_on_config_one(g_bf16):
+    """Config 1 (2^20 elements, 10 steps): the error of every arithmetic variant against the
+    oracle, printed (these are the figures quoted in the design notes) and held to the bars of
+    assert_state_close."""
+    from tests.gpu_util import state_errors
+    old = zc.tune_get("adam.arith")
+    try:
+        for arith in (0, 1, 2):
+            zc.tune_set("adam.arith", arith)
+            gpu, cpu = run_both(synth.TINY_N, 10, g_bf16=g_bf16, seed=1)
+            check(gpu, cpu, steps=10, tag=f"arith {arith}")
+            perr, merr, verr, m_bits, v_bits = state_errors(*gpu[:3], *cpu[:3])
+            print(f"config 1, {'bf16' if g_bf16 else 'fp32'} gradients, adam.arith={arith}: p {perr:.2f} ulp at max(|p|, lr), "
+                  f"m {merr:.2f} ulp, v {verr} ulp, elements with other bits: m {m_bits}, v {v_bits}")
+            if arith == 2:
+                assert (m_bits, v_bits) == (0, 0) and perr <= 1.0
+    finally:
+        zc.tune_set("adam.arith", old)
+
+
 @pytest.mark.parametrize("arith", [0, 2])
 def test_kernel_arithmetic_against_both_oracle_builds(arith):
     """The fp32 kernel variant sits next to the all-fp32 oracle build and the fp64 variant on
