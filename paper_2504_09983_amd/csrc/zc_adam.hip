@@ -6,15 +6,19 @@
 // a wave reads one contiguous 1 KiB row per instruction (lane l owns elements
 // 4l..4l+3 of the row), a workgroup owns ROWS rows of 4*BLOCK elements, and
 // all loads of a tile are issued before any arithmetic.  Measured on MI355X the
-// mixed read/write stream runs fastest with small workgroups (one or two
-// waves) and only ~8-12 waves resident per CU; more waves in flight widen the
-// window of DRAM pages touched at once and cost bandwidth.  The resident-wave
-// count is capped by asking for a slice of LDS that is never used.
+// mixed read/write stream runs fastest with one-wave workgroups of one row,
+// dispatched in tile order, and only ~12 waves resident per CU; more waves in
+// flight widen the window of DRAM pages touched at once and cost bandwidth.  The
+// resident-wave count is capped by asking for a slice of LDS that is never used.
+// Loads are non-temporal; stores are written through the L2 at once (buffer
+// stores with the nt and sc1 bits), so that a tile's results reach DRAM together
+// instead of whenever the cache evicts them.
 //
 // The arithmetic (paper: Adam with momentum and variance buffers in fp32 next
 // to fp32 master parameters; Experimental settings, Adaptive offloading) is
 // bias-corrected Adam with epsilon outside the square root and, in ZC_ADAMW
-// mode, decoupled weight decay applied to the old parameter.
+// mode, decoupled weight decay applied to the old parameter.  It is hidden
+// behind the memory traffic, so the default evaluates it in fp64.
 #include <cmath>
 
 #include "zc_internal.h"
@@ -70,7 +74,7 @@ static AdamScalars make_scalars(const zc_adam_hparams *hp)
 
 // ARITH 0: fp32 throughout (fused multiply-adds, correctly rounded sqrt / div).
 // ARITH 1: multiply-adds in fp64 (full rate on gfx950), sqrt and divide in fp32.
-// ARITH 2: fp64 throughout.
+// ARITH 2 (default): fp64 throughout; m and v as unfused IEEE double expressions.
 template <int ARITH>
 __device__ __forceinline__ void adam_elem(float &p, float &m, float &v, float g, const AdamScalars &s)
 {

@@ -5,7 +5,8 @@
 // per instruction.  Workgroups are single waves that each own one small tile and
 // are dispatched in tile order; the number of resident waves per CU is capped
 // (unused dynamic LDS) because on MI355X a mixed read/write stream loses
-// bandwidth when too many DRAM pages are open at once.
+// bandwidth when too many DRAM pages are open at once.  Loads are non-temporal,
+// stores are written through the L2 at once (stream_out_rsrc in zc_internal.h).
 #include <new>
 #include <vector>
 
