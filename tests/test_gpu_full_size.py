@@ -283,3 +283,66 @@ def test_single_segment_longer_than_2_to_32_elements():
     plan.destroy()
     del gathered, dst_full
     torch.cuda.empty_cache()
+
+
+def test_norm_cast_and_accumulation_at_the_70b_shard_size():
+    """The other streaming kernels at n = 8,819,213,312 (element indices past 2^33): every element
+    against torch used as a double-precision / RNE calculator in chunks (properties that hold at
+    any size), windows around the ends and around 2^32 against the oracle."""
+    _, n, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_70B), 8, 1)
+    g = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    synth.device_normal_(g, synth.G_STD, seed=2001)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    chunk = 1 << 28
+    # squared norm: the exact sum, accumulated in double chunk by chunk
+    zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
+    sync()
+    want = 0.0
+    for s in range(0, n, chunk):
+        want += float(g[s:min(n, s + chunk)].double().square().sum())
+    assert flag.item() == 0 and abs(norm.item() - want) <= 1.3e-7 * want, (norm.item(), want)
+    # one window's share of that sum against the oracle's own
+    w_sq, w_bad = oracle.grad_sqnorm(host_u16(g[(1 << 32) - 4096:(1 << 32) + 4096]))
+    assert w_bad == 0 and abs(w_sq - float(g[(1 << 32) - 4096:(1 << 32) + 4096].double().square().sum())) <= 1e-12 * w_sq
+    # a non-finite element beyond index 2^33 is seen, and only while it is inside n
+    at = (1 << 33) + 12345
+    keep = g[at].clone()
+    g[at] = float("inf")
+    zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
+    sync()
+    assert flag.item() == 1
+    zc.grad_sqnorm(g, zc.BF16, at, norm, flag)
+    sync()
+    assert flag.item() == 0
+    g[at] = keep
+    print("norm ok", flush=True)
+    # accumulation: acc + micro * scale in double, rounded once: torch's fp64 as the calculator
+    acc = torch.empty(n, dtype=torch.float32, device=DEV)
+    synth.device_normal_(acc, synth.G_STD, seed=2010)
+    wins = [(s, w) for s, w in windows_for(n, count=6, width=1 << 12, seed=21)]
+    before = [(host_f32(acc[s:s + w]).copy(), host_u16(g[s:s + w])) for s, w in wins]
+    ref_head = (acc[:chunk].double() + g[:chunk].double() * 0.25).float()
+    ref_tail = (acc[n - chunk:].double() + g[n - chunk:].double() * 0.25).float()
+    mid = (1 << 32) - chunk // 2
+    ref_mid = (acc[mid:mid + chunk].double() + g[mid:mid + chunk].double() * 0.25).float()
+    zc.grad_accumulate(acc, g, zc.BF16, n, 0.25)
+    sync()
+    assert torch.equal(acc[:chunk], ref_head) and torch.equal(acc[n - chunk:], ref_tail)
+    assert torch.equal(acc[mid:mid + chunk], ref_mid)
+    for (s, w), (a0, gb) in zip(wins, before):
+        oracle.grad_accumulate(a0, gb, 0.25)
+        assert np.array_equal(host_f32(acc[s:s + w]).view(np.uint32), a0.view(np.uint32)), f"accumulate window@{s}"
+    del ref_head, ref_tail, ref_mid
+    print("accumulate ok", flush=True)
+    # cast: RNE of every element (torch's narrowing as the library routine), oracle on windows
+    out = torch.zeros(n, dtype=torch.int16, device=DEV)
+    zc.cast_bf16(acc, out, n)
+    sync()
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        assert torch.equal(acc[s:e].to(torch.bfloat16).view(torch.int16), out[s:e]), f"cast chunk@{s}"
+    for s, w in wins:
+        assert np.array_equal(host_u16(out[s:s + w]), oracle.cast_bf16(host_f32(acc[s:s + w]))), f"cast window@{s}"
+    del g, acc, out
+    torch.cuda.empty_cache()
