@@ -198,8 +198,9 @@ zc_status zc_per_tensor_layout(const int64_t *numels, int64_t ntensors, int32_t 
  * zc_unshard_plan_create validates the HOST segment table (offsets and sizes
  * inside [0, gathered_numel], non-NULL 2-byte-aligned dst for non-empty
  * segments), and uploads a descriptor table to the current device.
- * Destination ranges must not overlap each other or the gathered buffer (not
- * checked).  The plan stays valid until destroyed; dst pointers are captured.
+ * Destination ranges must not overlap each other (checked at creation) or the
+ * gathered buffer (checked at every zc_unshard); ZC_ERR_INVALID_ARG otherwise.
+ * The plan stays valid until destroyed; dst pointers are captured.
  * zc_unshard enqueues one kernel; `gathered` is DEVICE uint16[gathered_numel],
  * 2-byte aligned.  An empty plan (nsegs == 0 or all numel == 0) is a no-op.
  */

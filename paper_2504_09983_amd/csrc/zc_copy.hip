@@ -7,7 +7,9 @@
 // (unused dynamic LDS) because on MI355X a mixed read/write stream loses
 // bandwidth when too many DRAM pages are open at once.  Loads are non-temporal,
 // stores are written through the L2 at once (stream_out_rsrc in zc_internal.h).
+#include <algorithm>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "zc_internal.h"
@@ -244,6 +246,7 @@ __global__ __launch_bounds__(kCopyBlock) void unshard_kernel(const uint16_t *__r
 }  // namespace zc
 
 struct zc_unshard_plan {
+    std::vector<std::pair<uintptr_t, uintptr_t>> dst_ranges;  // [lo, hi) of every non-empty destination, sorted
     zc::SegDesc *segs_dev = nullptr;
     int32_t *hint_dev = nullptr;
     int64_t nsegs = 0;
@@ -358,6 +361,24 @@ zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t 
         table.push_back(d);
     }
 
+    // Destinations must not overlap each other: sort their byte ranges and compare neighbours.
+    std::vector<std::pair<uintptr_t, uintptr_t>> ranges;
+    try {
+        ranges.reserve(table.size());
+        for (const SegDesc &d : table)
+            if (d.numel > 0)
+                ranges.emplace_back(reinterpret_cast<uintptr_t>(d.dst),
+                                    reinterpret_cast<uintptr_t>(d.dst) + 2 * (uintptr_t)d.numel);
+    } catch (const std::bad_alloc &) {
+        return fail(ZC_ERR_NOMEM, "cannot allocate the destination range table");
+    }
+    std::sort(ranges.begin(), ranges.end());
+    for (size_t k = 1; k < ranges.size(); ++k)
+        if (ranges[k].first < ranges[k - 1].second)
+            return fail(ZC_ERR_INVALID_ARG, "two destinations overlap (bytes [%#llx, %#llx) and [%#llx, %#llx))",
+                        (unsigned long long)ranges[k - 1].first, (unsigned long long)ranges[k - 1].second,
+                        (unsigned long long)ranges[k].first, (unsigned long long)ranges[k].second);
+
     // hint[k] = last segment whose first tile is <= k << kHintShift, for k = 0 .. groups
     const int64_t groups = (ntiles >> kHintShift) + 1;
     std::vector<int32_t> hints;
@@ -379,6 +400,7 @@ zc_status zc_unshard_plan_create(const zc_segment *segs, int64_t nsegs, int64_t 
     zc_unshard_plan *plan = new (std::nothrow) zc_unshard_plan;
     if (!plan)
         return fail(ZC_ERR_NOMEM, "cannot allocate the plan");
+    plan->dst_ranges.swap(ranges);
     plan->nsegs = nsegs;
     plan->ntiles = ntiles;
     plan->gathered_numel = gathered_numel;
@@ -417,6 +439,16 @@ zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void
         return fail(ZC_ERR_INVALID_ARG, "gathered is NULL");
     if (!aligned_to(gathered, 2))
         return fail(ZC_ERR_ALIGNMENT, "gathered must be 2-byte aligned");
+    {
+        // The gathered buffer must not overlap any destination: find the first destination
+        // that ends behind its start and see whether it begins before its end.
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(gathered);
+        const uintptr_t hi = lo + 2 * (uintptr_t)plan->gathered_numel;
+        auto it = std::upper_bound(plan->dst_ranges.begin(), plan->dst_ranges.end(), lo,
+                                   [](uintptr_t v, const std::pair<uintptr_t, uintptr_t> &r) { return v < r.second; });
+        if (it != plan->dst_ranges.end() && it->first < hi)
+            return fail(ZC_ERR_INVALID_ARG, "the gathered buffer overlaps a destination");
+    }
     int dev = 0;
     ZC_HIP(hipGetDevice(&dev));
     if (dev != plan->device)

@@ -368,44 +368,18 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
     const int nb = ctx->num_buffers;
     const int64_t nchunks = (n_streamed + ce - 1) / ce;
 
-    if (tune().offload_zero_copy == 2) {
-        // Staged reads, direct writes: a copy engine brings each chunk into a ring slot
-        // (large read requests on the link), the update kernel reads the slot from HBM and
-        // stores the new state straight into the pinned host arrays.  Nothing is copied
-        // back by the runtime, so only two streams take part and a slot is free again as
-        // soon as its kernel has finished.
-        float *pd = nullptr, *md = nullptr, *vd = nullptr;
+    // Transport 2 (staged reads, direct writes): a copy engine brings each chunk into a ring
+    // slot (large read requests on the link), the update kernel reads the slot from HBM and
+    // stores the new state straight into the pinned host arrays; nothing is copied back by
+    // the runtime, and a slot is free again as soon as its kernel has finished.
+    // Transport 0 (staged ring): the kernel updates the slot in place and a third stream
+    // copies it back.
+    const bool direct_writes = tune().offload_zero_copy == 2;
+    float *pd = nullptr, *md = nullptr, *vd = nullptr;
+    if (direct_writes) {
         ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&pd), p_host, 0));
         ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&md), m_host, 0));
         ZC_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&vd), v_host, 0));
-        for (int64_t k = 0; k < nchunks; ++k) {
-            const int slot = (int)(k % nb);
-            const int64_t off = k * ce;
-            const int64_t cnt = (n_streamed - off) < ce ? (n_streamed - off) : ce;
-            const size_t bytes = (size_t)cnt * 4;
-            float *sp = ctx->staging + (int64_t)slot * 3 * ce;
-            float *sm = sp + ce;
-            float *sv = sm + ce;
-            if (k >= nb) {
-                if (tune().offload_max_ahead > 0)
-                    ZC_HIP(hipEventSynchronize(ctx->freed[slot]));
-                ZC_HIP(hipStreamWaitEvent(ctx->h2d, ctx->freed[slot], 0));
-            }
-            ZC_HIP(hipMemcpyAsync(sp, p_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
-            ZC_HIP(hipMemcpyAsync(sm, m_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
-            ZC_HIP(hipMemcpyAsync(sv, v_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
-            ZC_HIP(hipEventRecord(ctx->loaded[slot], ctx->h2d));
-
-            ZC_HIP(hipStreamWaitEvent(stream, ctx->loaded[slot], 0));
-            const AdamOut to_host{pd + off, md + off, vd + off};
-            ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp,
-                               out_tail ? out_tail + off : nullptr, skip_flag, stream,
-                               (int)tune().offload_zc_waves_per_cu, nullptr, &to_host));
-            if (tune().offload_poison)
-                ZC_TRY(launch_poison(sp, 3 * ce, stream));
-            ZC_HIP(hipEventRecord(ctx->freed[slot], stream));
-        }
-        return ZC_OK;
     }
     for (int64_t k = 0; k < nchunks; ++k) {
         const int slot = (int)(k % nb);
@@ -417,8 +391,8 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
         float *sv = sm + ce;
 
         if (k >= nb) {
-            // Optional host throttle: do not run more than num_buffers chunks ahead of
-            // the copy-backs that have finished (the event still holds chunk k - nb's record).
+            // Optional host throttle: do not run more than num_buffers chunks ahead of the
+            // slots that have been released (the event still holds chunk k - nb's record).
             if (tune().offload_max_ahead > 0)
                 ZC_HIP(hipEventSynchronize(ctx->freed[slot]));
             ZC_HIP(hipStreamWaitEvent(ctx->h2d, ctx->freed[slot], 0));
@@ -427,28 +401,34 @@ zc_status zc_offload_adam_step(zc_offload_ctx *ctx, float *p_dev, float *m_dev, 
         ZC_HIP(hipMemcpyAsync(sm, m_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
         ZC_HIP(hipMemcpyAsync(sv, v_host + off, bytes, hipMemcpyHostToDevice, ctx->h2d));
         ZC_HIP(hipEventRecord(ctx->loaded[slot], ctx->h2d));
-
         ZC_HIP(hipStreamWaitEvent(stream, ctx->loaded[slot], 0));
-        ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp,
-                           out_tail ? out_tail + off : nullptr, skip_flag, stream));
-        ZC_HIP(hipEventRecord(ctx->updated[slot], stream));
 
-        hipStream_t back = ctx->d2h;
-        if (tune().offload_d2h_on_compute)
-            back = stream;  // copy-back in order behind the kernel, no cross-stream wait
-        else
-            ZC_HIP(hipStreamWaitEvent(ctx->d2h, ctx->updated[slot], 0));
-        ZC_HIP(hipMemcpyAsync(p_host + off, sp, bytes, hipMemcpyDeviceToHost, back));
-        ZC_HIP(hipMemcpyAsync(m_host + off, sm, bytes, hipMemcpyDeviceToHost, back));
-        ZC_HIP(hipMemcpyAsync(v_host + off, sv, bytes, hipMemcpyDeviceToHost, back));
+        uint16_t *out_k = out_tail ? out_tail + off : nullptr;
+        hipStream_t releases = stream;           // the stream whose progress frees the slot
+        if (direct_writes) {
+            const AdamOut to_host{pd + off, md + off, vd + off};
+            ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp, out_k, skip_flag, stream,
+                               (int)tune().offload_zc_waves_per_cu, nullptr, &to_host));
+        } else {
+            ZC_TRY(launch_adam(sp, sm, sv, g_tail + off * g_size, g_dtype, cnt, hp, out_k, skip_flag, stream));
+            ZC_HIP(hipEventRecord(ctx->updated[slot], stream));
+            if (!tune().offload_d2h_on_compute) {    // else: copy back in order behind the kernel
+                releases = ctx->d2h;
+                ZC_HIP(hipStreamWaitEvent(ctx->d2h, ctx->updated[slot], 0));
+            }
+            ZC_HIP(hipMemcpyAsync(p_host + off, sp, bytes, hipMemcpyDeviceToHost, releases));
+            ZC_HIP(hipMemcpyAsync(m_host + off, sm, bytes, hipMemcpyDeviceToHost, releases));
+            ZC_HIP(hipMemcpyAsync(v_host + off, sv, bytes, hipMemcpyDeviceToHost, releases));
+        }
         if (tune().offload_poison)
-            ZC_TRY(launch_poison(sp, 3 * ce, back));
-        ZC_HIP(hipEventRecord(ctx->freed[slot], back));
+            ZC_TRY(launch_poison(sp, 3 * ce, releases));
+        ZC_HIP(hipEventRecord(ctx->freed[slot], releases));
     }
-
-    // The caller's stream resumes only after the last copy-back has landed.
-    ZC_HIP(hipEventRecord(ctx->done, ctx->d2h));
-    ZC_HIP(hipStreamWaitEvent(stream, ctx->done, 0));
+    if (!direct_writes) {
+        // The caller's stream resumes only after the last copy-back has landed.
+        ZC_HIP(hipEventRecord(ctx->done, ctx->d2h));
+        ZC_HIP(hipStreamWaitEvent(stream, ctx->done, 0));
+    }
     return ZC_OK;
 }
 

@@ -179,6 +179,19 @@ def test_unshard_model_shaped_scaled_down():
     assert 8 * shard > total
 
 
+def test_unshard_refuses_a_gathered_buffer_that_overlaps_a_destination():
+    buf = torch.zeros(4096, dtype=torch.int16, device=DEV)
+    other = torch.zeros(1024, dtype=torch.int16, device=DEV)
+    plan = zc.unshard_plan_create([(0, buf[1024:2048], 1024), (1024, other, 1024)], 2048)
+    for gathered in (buf[:2048], buf[1500:3548], buf[2047:]):          # share bytes with buf[1024:2048]
+        with pytest.raises(zc.ZcError) as e:
+            zc.unshard(plan, gathered)
+        assert e.value.status == zc.ERR_INVALID_ARG and "overlaps" in e.value.message
+    zc.unshard(plan, buf[2048:])                                        # touching is fine
+    sync()
+    plan.destroy()
+
+
 def test_empty_plan_is_a_noop():
     plan = zc.unshard_plan_create([], 0)
     zc.unshard(plan, None)

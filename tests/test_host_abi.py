@@ -121,6 +121,11 @@ def test_unshard_plan_and_offload_reject_bad_arguments_without_a_gpu():
     assert _status(zc.UnshardPlan, [(0, A + 1, 4)], 100) == zc.ERR_ALIGNMENT
     assert _status(zc.UnshardPlan, [(0, A, 4)], -1) == zc.ERR_INVALID_ARG
     assert "segment" in zc.last_error() or "gathered" in zc.last_error()
+    # destinations that share bytes are refused, whatever the order they come in; touching is fine
+    assert _status(zc.UnshardPlan, [(0, A, 8), (8, A + 14, 8)], 100) == zc.ERR_INVALID_ARG
+    assert "overlap" in zc.last_error()
+    assert _status(zc.UnshardPlan, [(8, A + 64, 8), (0, A, 40)], 100) == zc.ERR_INVALID_ARG
+    assert _status(zc.UnshardPlan, [(0, A, 8), (8, A, 8)], 100) == zc.ERR_INVALID_ARG
     assert _status(zc.OffloadCtx, 1000, 3) == zc.ERR_INVALID_ARG
     assert _status(zc.OffloadCtx, 1 << 20, 0) == zc.ERR_INVALID_ARG
     assert _status(zc.OffloadCtx, 1 << 20, 9) == zc.ERR_INVALID_ARG
