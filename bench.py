@@ -592,6 +592,10 @@ def offload_leg(torch, synth, zc, dev, args, link):
         b.free()
     out.update(link)
     best = out["zero_copy"][f"f={fracs[0]:g}"]["link_GBps_each_direction"]
+    out["roofline"] = {"bound": "host link (PCIe Gen5 x16), each direction", "kernel": "zc::adam_vec_kernel over pinned host p/m/v",
+                       "achieved": best, "peak": PCIE_PEAK_GBS, "unit": "GB/s", "frac": round(best / PCIE_PEAK_GBS, 4),
+                       "algorithmic_bytes_per_element_each_way": 12, "target_frac": 0.80, "below_target": True}
+    out["roofline"]["below_target"] = out["roofline"]["frac"] < 0.80
     out["headline"] = {"transport": "zero_copy", "link_GBps_each_direction": best,
                        "frac_of_link_peak_63": round(best / PCIE_PEAK_GBS, 4),
                        "frac_of_duplex_memcpy_ceiling": round(best / out["memcpy_ceiling_GBps"]["both_each"], 4),
