@@ -536,7 +536,8 @@ static zc_status check_adam_args(float *p, float *m, float *v, const void *g, zc
         return fail(ZC_ERR_ALIGNMENT, "bf16_out must be 2-byte aligned");
     if (skip_flag && !aligned_to(skip_flag, 4))
         return fail(ZC_ERR_ALIGNMENT, "skip_flag must be 4-byte aligned");
-    // The kernel reads every array through __restrict__ pointers: no two may share a byte.
+    // Every lane reads its own elements and then writes them; an array that shared bytes with
+    // another would be read by one lane after another lane has written it.  No two may overlap.
     struct Span { uintptr_t lo, hi; };
     const uintptr_t n4 = (uintptr_t)n * 4, ng = (uintptr_t)n * (g_dtype == ZC_BF16 ? 2 : 4);
     const Span spans[5] = {{(uintptr_t)p, (uintptr_t)p + n4}, {(uintptr_t)m, (uintptr_t)m + n4},
