@@ -6,7 +6,10 @@ paper evaluates (Evaluation, Experimental settings), one after the other:
 
   headline   Llama-3-70B-shaped one-of-8 shard, 8,819,213,312 fp32 elements, 141 GB resident:
                  zc_grad_sqnorm  (overflow flag + squared norm of the bf16 gradient shard)
-                 zc_adam_step    (fused AdamW, bf16 copy into the send buffer, skipped on overflow)
+                 zc_adam_step_packed (fused AdamW over the packed p/m/v state array, bf16 copy into
+                                 the send buffer, skipped on overflow; --state-layout arrays times
+                                 zc_adam_step over three separate arrays instead, and the default
+                                 run reports that one beside it)
              `value` = shard elements / wall time of one such step.  The unshard copy of this
              model (141 GB gathered + 141 GB of tensors) does not fit next to the step's state,
              so row a3 of the path is timed at its own largest size:
@@ -49,6 +52,10 @@ def parse_args():
                     choices=["headline", "llama3_8b", "llama3_70b", "mixtral_8x7b", "tiny"],
                     help="headline = 70B shard step + Mixtral unshard + 8B whole step (default); "
                          "a model name = that model's shard only")
+    ap.add_argument("--state-layout", default="packed", choices=["packed", "arrays"],
+                    help="how the timed step holds p, m, v: the library's packed state array "
+                         "(zc_adam_step_packed, default) or three arrays (zc_adam_step); the other one "
+                         "is timed beside it unless --no-next-rows")
     ap.add_argument("--no-unshard", action="store_true",
                     help="single-model workloads: leave the unshard copy out")
     ap.add_argument("--only-unshard", action="store_true",
@@ -113,20 +120,40 @@ def shard_of(zc, synth, workload):
     return tensors, numels
 
 
-def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, with_step=True, variants=False):
+def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, with_step=True, variants=False,
+               layout="packed"):
     """grad-norm + fused AdamW with bf16 copy (+ unshard of the 8-shard gathered buffer) on one
-    model's one-of-8 shard.  Returns (record, seconds of the timed region)."""
+    model's one-of-8 shard.  `layout`: "packed" keeps p, m, v in the library's granule-interleaved
+    state array (zc_adam_step_packed), "arrays" in three separate arrays (zc_adam_step).
+    Returns (record, seconds of the timed region)."""
     tensors, numels = shard_of(zc, synth, workload)
     offs, shard, total = zc.flat_layout(numels, WORLD, 1)
     n = shard
     hp_kw = dict(synth.HP)
+    packed = layout == "packed"
     if with_step:
-        p = torch.empty(n, dtype=torch.float32, device=dev)
-        m = torch.zeros(n, dtype=torch.float32, device=dev)
-        v = torch.zeros(n, dtype=torch.float32, device=dev)
+        if packed:
+            state = torch.empty(zc.packed_state_numel(n), dtype=torch.float32, device=dev)
+            cube = state.view(-1, 3, zc.PACKED_GRANULE)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(2)
+            for k in range(0, cube.shape[0], 1 << 12):          # p ~ N(0, sigma); m = v = 0
+                rows = min(1 << 12, cube.shape[0] - k)
+                cube[k:k + rows, 0] = torch.randn(rows, zc.PACKED_GRANULE, generator=gen, device=dev) * synth.P_STD
+            cube[:, 1:].zero_()
+        else:
+            p = torch.empty(n, dtype=torch.float32, device=dev)
+            m = torch.zeros(n, dtype=torch.float32, device=dev)
+            v = torch.zeros(n, dtype=torch.float32, device=dev)
+            synth.device_normal_(p, synth.P_STD, seed=2)
         g = torch.empty(n, dtype=torch.bfloat16, device=dev)
-        synth.device_normal_(p, synth.P_STD, seed=2)
         synth.device_normal_(g, synth.G_STD, seed=2001)
+
+    def update(grad, dtype, hp, **kw):
+        if packed:
+            zc.adam_step_packed(state, grad, dtype, n, hp, **kw)
+        else:
+            zc.adam_step(p, m, v, grad, dtype, n, hp, **kw)
     norm = torch.zeros(1, dtype=torch.float32, device=dev)
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
     if with_unshard:
@@ -148,7 +175,7 @@ def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, wit
             zc.grad_sqnorm(g, zc.BF16, n, norm, flag)
         if ev: ev[1].record()
         if with_step:
-            zc.adam_step(p, m, v, g, zc.BF16, n, hp, bf16_out=send, skip_flag=flag)
+            update(g, zc.BF16, hp, bf16_out=send, skip_flag=flag)
         if ev: ev[2].record()
         if with_unshard:
             zc.unshard(plan, gathered)
@@ -176,6 +203,8 @@ def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, wit
     if with_unshard:
         kernels["unshard"] = kernel_record("zc::unshard_kernel", times(2), 4 * total, total, 4)
     rec = {"workload": workload, "shard_elements": n, "model_elements": total, "tensors": len(numels),
+           "state_layout": ("one packed array (granules of %d elements of p, m, v)" % zc.PACKED_GRANULE) if packed
+           else "three arrays",
            "ms_per_step": round(wall * 1e3 / steps, 4),
            "gparams_per_s": round(n / (wall / steps) / 1e9, 3), "kernels": kernels}
 
@@ -187,14 +216,15 @@ def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, wit
         g32 = torch.empty(n, dtype=torch.float32, device=dev)
         synth.device_normal_(g32, synth.G_STD, seed=2999)
         rows = {
-            "bf16_grads_fused_copy": (28, lambda: zc.adam_step(p, m, v, g, zc.BF16, n, hp_next(), bf16_out=send)),
-            "bf16_grads_no_copy": (26, lambda: zc.adam_step(p, m, v, g, zc.BF16, n, hp_next())),
-            "fp32_grads_fused_copy": (30, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next(), bf16_out=send)),
-            "fp32_grads_no_copy": (28, lambda: zc.adam_step(p, m, v, g32, zc.F32, n, hp_next())),
-            "unfused_step_then_cast": (32, lambda: (zc.adam_step(p, m, v, g, zc.BF16, n, hp_next()),
-                                                    zc.cast_bf16(p, send, n))),
-            "standalone_cast": (6, lambda: zc.cast_bf16(p, send, n)),
+            "bf16_grads_fused_copy": (28, lambda: update(g, zc.BF16, hp_next(), bf16_out=send)),
+            "bf16_grads_no_copy": (26, lambda: update(g, zc.BF16, hp_next())),
+            "fp32_grads_fused_copy": (30, lambda: update(g32, zc.F32, hp_next(), bf16_out=send)),
+            "fp32_grads_no_copy": (28, lambda: update(g32, zc.F32, hp_next())),
         }
+        if not packed:                 # the standalone cast reads a contiguous p
+            rows["unfused_step_then_cast"] = (32, lambda: (zc.adam_step(p, m, v, g, zc.BF16, n, hp_next()),
+                                                           zc.cast_bf16(p, send, n)))
+            rows["standalone_cast"] = (6, lambda: zc.cast_bf16(p, send, n))
         rec["step_variants"] = {}
         for name, (bpe, fn) in rows.items():
             ms = time_launches(torch, fn, reps=10 if n < (1 << 32) else 5)
@@ -207,7 +237,11 @@ def step_phase(torch, synth, zc, dev, workload, steps, warmup, with_unshard, wit
         plan.destroy()
         del outs, gathered
     if with_step:
-        del p, m, v, g
+        if packed:
+            del state, cube
+        else:
+            del p, m, v
+        del g
     del send
     torch.cuda.empty_cache()
     return rec, wall
@@ -300,7 +334,12 @@ def main():
     extra = {}
     if args.workload == "headline":
         head, wall = step_phase(torch, synth, zc, dev, "llama3_70b", args.steps, args.warmup,
-                                with_unshard=False, variants=not args.no_next_rows)
+                                with_unshard=False, variants=not args.no_next_rows, layout=args.state_layout)
+        if not args.no_next_rows:
+            other = "arrays" if args.state_layout == "packed" else "packed"
+            alt, _ = step_phase(torch, synth, zc, dev, "llama3_70b", args.steps, args.warmup,
+                                with_unshard=False, variants=True, layout=other)
+            extra["llama3_70b_with_" + ("three_state_arrays" if other == "arrays" else "packed_state")] = alt
         unsh, _ = step_phase(torch, synth, zc, dev, "mixtral_8x7b", args.steps, args.warmup,
                              with_unshard=True, with_step=False)
         kernels = dict(head["kernels"])
@@ -309,8 +348,13 @@ def main():
         extra["unshard_mixtral_8x7b"]["gathered_elements"] = \
             WORLD * zc.flat_layout(shard_of(zc, synth, "mixtral_8x7b")[1], WORLD, 1)[1]
         small, _ = step_phase(torch, synth, zc, dev, "llama3_8b", args.steps, args.warmup,
-                              with_unshard=True, variants=not args.no_next_rows)
+                              with_unshard=True, variants=not args.no_next_rows, layout=args.state_layout)
         extra["whole_step_llama3_8b"] = small
+        if not args.no_next_rows:
+            other = "arrays" if args.state_layout == "packed" else "packed"
+            alt, _ = step_phase(torch, synth, zc, dev, "llama3_8b", args.steps, args.warmup,
+                                with_unshard=False, variants=True, layout=other)
+            extra["llama3_8b_with_" + ("three_state_arrays" if other == "arrays" else "packed_state")] = alt
         workload_text = ("llama3_70b one-of-8 shard: grad-norm + fused AdamW with bf16 copy (141 GB resident); "
                          "unshard timed on the mixtral_8x7b gathered buffer of 8 shards (46.7 B elements -> 995 "
                          "tensors), which does not fit beside the 70B step")
@@ -318,7 +362,8 @@ def main():
         do_unshard = not args.no_unshard
         do_step = not args.only_unshard
         head, wall = step_phase(torch, synth, zc, dev, args.workload, args.steps, args.warmup,
-                                with_unshard=do_unshard, with_step=do_step, variants=not args.no_next_rows)
+                                with_unshard=do_unshard, with_step=do_step, variants=not args.no_next_rows,
+                                layout=args.state_layout)
         kernels = dict(head["kernels"])
         workload_text = (f"{args.workload} one-of-{WORLD} shard: "
                          + ("grad-norm + fused AdamW with bf16 copy" if do_step else "")
@@ -336,7 +381,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         try:
-            rec = json.load(open(tpath)).get(dom_workload, {}).get(dominant)
+            key = "adam_packed" if (dominant == "adam" and args.state_layout == "packed") else dominant
+            rec = json.load(open(tpath)).get(dom_workload, {}).get(key)
             if rec:
                 traffic = rec["fetch_bytes"] + rec["write_bytes"]
                 traffic_source = ("profiles/pmc_traffic.json: FETCH_SIZE and WRITE_SIZE of this kernel at this "
@@ -359,7 +405,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "f32", 1: "f32+f64", 2: "f64"}[zc.tune_get("adam.arith")], "data": "synthetic",
         "config": {"workload": workload_text, "shard_elements": n, "model_elements": head["model_elements"],
-                   "tensors": head["tensors"], "grads": "bf16", "state": "fp32 p/m/v resident in HBM",
+                   "tensors": head["tensors"], "grads": "bf16",
+                   "state": "fp32 p/m/v resident in HBM, " + head["state_layout"],
                    "tuning": tuning},
         "roofline": roofline,
         "kernels": kernels,

@@ -115,3 +115,59 @@ def per_tensor_segments(numels, world: int, align: int = 1):
             if k > 0:
                 segs.append((t, r * L + o, r * s, k))
     return segs, L
+
+
+# ---------------------------------------------------------------------------
+# Packed optimizer state (a layout of this build, not of the paper: the paper
+# only fixes that a rank keeps fp32 parameters, momentum and variance;
+# Experimental settings).  Definition: the partition is cut into granules of G
+# elements; granule k of p, then granule k of m, then granule k of v follow
+# each other, for k = 0, 1, ...; the last granule is padded with zeros.
+# ---------------------------------------------------------------------------
+
+def packed_state_numel(n: int, granule: int) -> int:
+    """Floats in the packed array of an n-element partition."""
+    if granule < 1:
+        raise ValueError("granule must be positive")
+    if n <= 0:
+        return 0
+    return 3 * (-(-int(n) // granule)) * granule
+
+
+def pack_state(p, m, v, granule: int):
+    """The packed array, built granule by granule exactly as the definition reads."""
+    p = np.asarray(p, dtype=np.float32)
+    m = np.asarray(m, dtype=np.float32)
+    v = np.asarray(v, dtype=np.float32)
+    n = p.size
+    if m.size != n or v.size != n:
+        raise ValueError("p, m, v differ in length")
+    out = np.zeros(packed_state_numel(n, granule), dtype=np.float32)
+    k = 0
+    while k * granule < n:
+        lo, hi = k * granule, min((k + 1) * granule, n)
+        base = 3 * k * granule
+        out[base:base + (hi - lo)] = p[lo:hi]
+        out[base + granule:base + granule + (hi - lo)] = m[lo:hi]
+        out[base + 2 * granule:base + 2 * granule + (hi - lo)] = v[lo:hi]
+        k += 1
+    return out
+
+
+def unpack_state(state, n: int, granule: int):
+    """(p, m, v) read back out of a packed array, granule by granule."""
+    state = np.asarray(state, dtype=np.float32)
+    if state.size != packed_state_numel(n, granule):
+        raise ValueError("packed array has the wrong length")
+    p = np.empty(n, dtype=np.float32)
+    m = np.empty(n, dtype=np.float32)
+    v = np.empty(n, dtype=np.float32)
+    k = 0
+    while k * granule < n:
+        first, count = k * granule, min(granule, n - k * granule)
+        start = 3 * k * granule
+        p[first:first + count] = state[start:start + count]
+        m[first:first + count] = state[start + granule:start + granule + count]
+        v[first:first + count] = state[start + 2 * granule:start + 2 * granule + count]
+        k += 1
+    return p, m, v

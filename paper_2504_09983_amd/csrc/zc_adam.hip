@@ -41,6 +41,24 @@ struct DevCtl {
     const float *gscale;
 };
 
+// Packed state (zc_adam_step_packed): p, m and v of one partition interleaved in granules of
+// ZC_PACKED_GRANULE elements, [p granule 0][m granule 0][v granule 0][p granule 1]...  Element e
+// of p sits at state[packed_at(e)], its m one granule and its v two granules behind it.
+constexpr int kGranuleShift = 13;
+constexpr int64_t kGranule = int64_t(1) << kGranuleShift;
+constexpr int64_t kGranuleVecs = kGranule / 4;
+static_assert(kGranule == ZC_PACKED_GRANULE, "the header and the kernels must agree on the granule");
+
+__host__ __device__ __forceinline__ int64_t packed_at(int64_t e)
+{
+    return e + ((e >> kGranuleShift) << (kGranuleShift + 1));
+}
+// the same for an index in 16-byte vectors
+__host__ __device__ __forceinline__ int64_t packed_vec_at(int64_t gv)
+{
+    return gv + ((gv >> (kGranuleShift - 2)) << (kGranuleShift - 1));
+}
+
 static AdamScalars make_scalars(const zc_adam_hparams *hp)
 {
     AdamScalars s;
@@ -163,11 +181,16 @@ __device__ __forceinline__ void st(T *ptr, T val)
 
 // NT: 0 = ordinary loads and stores, 1 = both non-temporal, 2 = loads only, 3 = stores only,
 // 4 = non-temporal loads and write-through streaming stores (stream_out_rsrc, zc_internal.h).
-template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH, bool GUARD>
+// PACKED: p4 == po4 is the packed state array (m4, v4, mo4, vo4 unused) and gv0 the index, in
+// vectors of the flat partition, of the stretch's first element; g and out2 stay flat.  A tile
+// may straddle a granule boundary (a stretch can start anywhere), so every lane maps its own
+// vector and the store descriptors span the tile's first to its last packed vector.
+template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH, bool GUARD, bool PACKED = false>
 __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, const f32x4 *v4,
                                           f32x4 *po4, f32x4 *mo4, f32x4 *vo4,
                                           const void *__restrict__ g, u32x2 *__restrict__ out2,
-                                          int64_t first, int64_t nvec, const AdamScalars &s_in, DevCtl ctl)
+                                          int64_t first, int64_t nvec, const AdamScalars &s_in, DevCtl ctl,
+                                          int64_t gv0 = 0)
 {
     // The skip flag and the device-side scale are fetched together with the data and only
     // used after the tile's loads have been issued, so their latency hides behind them.
@@ -180,12 +203,21 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
     constexpr int64_t kTileVecs = (int64_t)BLOCK * ROWS;
     const int64_t tile_first = first - threadIdx.x;
     __amdgpu_buffer_rsrc_t rp, rm, rv, ro;
+    int64_t packed_first = 0;                        // packed vector index of the tile's first vector
     if constexpr (NT == 4) {
         int64_t vecs = nvec - tile_first;            // whole 16-byte vectors this tile may write
         vecs = vecs < 0 ? 0 : (vecs > kTileVecs ? kTileVecs : vecs);
-        rp = stream_out_rsrc(po4 + tile_first, vecs * 16);
-        rm = stream_out_rsrc(mo4 + tile_first, vecs * 16);
-        rv = stream_out_rsrc(vo4 + tile_first, vecs * 16);
+        if constexpr (PACKED) {
+            packed_first = packed_vec_at(gv0 + tile_first);
+            const int64_t span = vecs > 0 ? packed_vec_at(gv0 + tile_first + vecs - 1) - packed_first + 1 : 0;
+            rp = stream_out_rsrc(po4 + packed_first, span * 16);
+            rm = stream_out_rsrc(po4 + packed_first + kGranuleVecs, span * 16);
+            rv = stream_out_rsrc(po4 + packed_first + 2 * kGranuleVecs, span * 16);
+        } else {
+            rp = stream_out_rsrc(po4 + tile_first, vecs * 16);
+            rm = stream_out_rsrc(mo4 + tile_first, vecs * 16);
+            rv = stream_out_rsrc(vo4 + tile_first, vecs * 16);
+        }
         ro = stream_out_rsrc(out2 ? (void *)(out2 + tile_first) : (void *)po4, out2 ? vecs * 8 : 0);
     }
     f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
@@ -193,9 +225,16 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
     for (int r = 0; r < ROWS; ++r) {
         const int64_t i = first + (int64_t)r * BLOCK;
         if (!GUARD || i < nvec) {
-            pv[r] = ld<NTL>(p4 + i);
-            mv[r] = ld<NTL>(m4 + i);
-            vv[r] = ld<NTL>(v4 + i);
+            if constexpr (PACKED) {
+                const f32x4 *at = p4 + packed_vec_at(gv0 + i);
+                pv[r] = ld<NTL>(at);
+                mv[r] = ld<NTL>(at + kGranuleVecs);
+                vv[r] = ld<NTL>(at + 2 * kGranuleVecs);
+            } else {
+                pv[r] = ld<NTL>(p4 + i);
+                mv[r] = ld<NTL>(m4 + i);
+                vv[r] = ld<NTL>(v4 + i);
+            }
             if constexpr (G_BF16) {
                 const u32x2 w = ld<NTL>(reinterpret_cast<const u32x2 *>(g) + i);
                 gv[r].x = __uint_as_float(w.x << 16);
@@ -228,9 +267,10 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
             }
             if constexpr (NT == 4) {
                 const int voff = (int)(threadIdx.x + r * BLOCK) * 16;
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, pv[r]), rp, voff, 0, kAuxStreamOut);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, mv[r]), rm, voff, 0, kAuxStreamOut);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, vv[r]), rv, voff, 0, kAuxStreamOut);
+                const int soff = PACKED ? (int)(packed_vec_at(gv0 + i) - packed_first) * 16 : voff;
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, pv[r]), rp, soff, 0, kAuxStreamOut);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, mv[r]), rm, soff, 0, kAuxStreamOut);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, vv[r]), rv, soff, 0, kAuxStreamOut);
                 if (out2) {
                     u32x2v w;
                     w[0] = bf16_rne(pv[r].x) | (bf16_rne(pv[r].y) << 16);
@@ -238,6 +278,7 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
                     __builtin_amdgcn_raw_buffer_store_b64(w, ro, voff >> 1, 0, kAuxStreamOut);
                 }
             } else {
+                static_assert(!PACKED, "the packed layout is built with streaming stores only");
                 st<NTS>(po4 + i, pv[r]);
                 st<NTS>(mo4 + i, mv[r]);
                 st<NTS>(vo4 + i, vv[r]);
@@ -259,12 +300,15 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
 // The new state goes to po, mo, vo: the same arrays for the in-place step, or other arrays
 // of the same alignment (the offloaded step reads staged copies and writes host memory).
 // Each element is read before it is written and by the same lane, so p == po needs no care.
-template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH>
+// PACKED: p == po is the packed state array, m, v, mo, vo are unused, and e0 is the index in
+// the flat partition of the stretch's first element (a multiple of 4).
+template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH, bool PACKED = false>
 __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(const float *p, const float *m, const float *v,
                                                          float *po, float *mo, float *vo,
                                                          const void *__restrict__ g,
                                                          uint16_t *__restrict__ out, int64_t n,
-                                                         int64_t tile0, AdamScalars s, DevCtl ctl)
+                                                         int64_t tile0, AdamScalars s, DevCtl ctl,
+                                                         int64_t e0 = 0)
 {
     const int64_t nvec = n >> 2;
     const f32x4 *p4 = reinterpret_cast<const f32x4 *>(p);
@@ -279,9 +323,11 @@ __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(const float *p, const f
     const int64_t tile = tile0 + blockIdx.x;
     const int64_t first = tile * kTileVecs + threadIdx.x;
     if ((tile + 1) * kTileVecs <= nvec)
-        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false>(p4, m4, v4, po4, mo4, vo4, g, out2, first, nvec, s, ctl);
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, false, PACKED>(p4, m4, v4, po4, mo4, vo4, g, out2, first, nvec,
+                                                                 s, ctl, e0 >> 2);
     else
-        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true>(p4, m4, v4, po4, mo4, vo4, g, out2, first, nvec, s, ctl);
+        adam_tile<ROWS, BLOCK, G_BF16, NT, ARITH, true, PACKED>(p4, m4, v4, po4, mo4, vo4, g, out2, first, nvec,
+                                                                s, ctl, e0 >> 2);
 
     // The last n % 4 elements, one lane each, in the very first workgroup.
     const int64_t i = (nvec << 2) + threadIdx.x;
@@ -290,28 +336,35 @@ __global__ __launch_bounds__(BLOCK) void adam_vec_kernel(const float *p, const f
             s.gscalef = s.gscalef * *ctl.gscale;
             s.gscale = (double)s.gscalef;
         }
-        float pe = p[i], me = m[i], ve = v[i];
+        const int64_t ip = PACKED ? packed_at(e0 + i) : i;
+        const int64_t im = PACKED ? ip + kGranule : i, iv = PACKED ? ip + 2 * kGranule : i;
+        if constexpr (PACKED) {
+            m = p, v = p;
+            mo = po, vo = po;
+        }
+        float pe = p[ip], me = m[im], ve = v[iv];
         float ge;
         if constexpr (G_BF16)
             ge = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16);
         else
             ge = reinterpret_cast<const float *>(g)[i];
         adam_elem<ARITH>(pe, me, ve, ge, s);
-        po[i] = pe;
-        mo[i] = me;
-        vo[i] = ve;
+        po[ip] = pe;
+        mo[im] = me;
+        vo[iv] = ve;
         if (out)
             out[i] = (uint16_t)bf16_rne(pe);
     }
 }
 
-// Any natural alignment: one element per lane, grid-stride.
+// Any natural alignment: one element per lane, grid-stride.  e0 >= 0: p == po is a packed
+// state array and e0 the flat index of the stretch's first element (m, v, mo, vo unused).
 template <bool G_BF16, int ARITH>
 __global__ __launch_bounds__(256) void adam_scalar_kernel(const float *p, const float *m, const float *v,
                                                           float *po, float *mo, float *vo,
                                                           const void *__restrict__ g,
                                                           uint16_t *__restrict__ out, int64_t n,
-                                                          AdamScalars s, DevCtl ctl)
+                                                          AdamScalars s, DevCtl ctl, int64_t e0)
 {
     if (ctl.skip && *ctl.skip != 0)
         return;
@@ -319,18 +372,25 @@ __global__ __launch_bounds__(256) void adam_scalar_kernel(const float *p, const 
         s.gscalef = s.gscalef * *ctl.gscale;
         s.gscale = (double)s.gscalef;
     }
+    const bool packed = e0 >= 0;
+    if (packed) {
+        m = p, v = p;
+        mo = po, vo = po;
+    }
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
-        float pe = p[i], me = m[i], ve = v[i];
+        const int64_t ip = packed ? packed_at(e0 + i) : i;
+        const int64_t im = packed ? ip + kGranule : i, iv = packed ? ip + 2 * kGranule : i;
+        float pe = p[ip], me = m[im], ve = v[iv];
         float ge;
         if constexpr (G_BF16)
             ge = __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(g)[i] << 16);
         else
             ge = reinterpret_cast<const float *>(g)[i];
         adam_elem<ARITH>(pe, me, ve, ge, s);
-        po[i] = pe;
-        mo[i] = me;
-        vo[i] = ve;
+        po[ip] = pe;
+        mo[im] = me;
+        vo[iv] = ve;
         if (out)
             out[i] = (uint16_t)bf16_rne(pe);
     }
@@ -347,6 +407,7 @@ struct VecLaunch {
     int64_t n, tile0;
     AdamScalars s;
     DevCtl ctl;
+    int64_t e0 = 0;   // packed launches: flat index of the stretch's first element
 };
 
 template <int ROWS, int BLOCK, bool G_BF16, int NT, int ARITH>
@@ -354,7 +415,7 @@ static void launch_vec(const VecLaunch &a)
 {
     hipLaunchKernelGGL((adam_vec_kernel<ROWS, BLOCK, G_BF16, NT, ARITH>), a.grid, dim3(BLOCK), a.lds,
                        a.stream, a.p, a.m, a.v, a.po, a.mo, a.vo, a.g, a.out, a.n, a.tile0, a.s,
-                       a.ctl);
+                       a.ctl, (int64_t)0);
 }
 
 template <int ROWS, int BLOCK, bool G_BF16, int NT>
@@ -396,7 +457,7 @@ static void pick_rows(int rows, bool g_bf16, int nt, int arith, const VecLaunch 
 static void launch_scalar(const float *p, const float *m, const float *v, float *po, float *mo, float *vo,
                           const void *g, bool g_bf16, int64_t n,
                           uint16_t *bf16_out, const AdamScalars &s, DevCtl ctl, int arith, int cus,
-                          hipStream_t stream)
+                          hipStream_t stream, int64_t e0 = -1)
 {
     int64_t blocks = (n + 255) / 256;
     const int64_t cap = (int64_t)cus * 32;
@@ -405,7 +466,7 @@ static void launch_scalar(const float *p, const float *m, const float *v, float 
     const dim3 grid((unsigned)blocks);
 #define ZC_SCALAR(GB, AR)                                                                             \
     hipLaunchKernelGGL((adam_scalar_kernel<GB, AR>), grid, dim3(256), 0, stream, p, m, v, po, mo, vo, \
-                       g, bf16_out, n, s, ctl)
+                       g, bf16_out, n, s, ctl, e0)
     if (g_bf16) {
         if (arith == 0) ZC_SCALAR(true, 0);
         else if (arith == 1) ZC_SCALAR(true, 1);
@@ -511,6 +572,80 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
     return ZC_OK;
 }
 
+// The update over elements [e0, e0 + n) of a packed state array; g and bf16_out point at the
+// stretch's first element.  One-wave workgroups of one row with streaming stores and the
+// default arithmetic: the shape every size ran fastest with; only the resident-wave cap is
+// taken from the knobs.  The state array is 128-byte aligned and a granule is a whole number
+// of lines, so the alignment of element e inside the array is that of 4*e.
+static zc_status launch_adam_packed(float *state, int64_t e0, const void *g, zc_dtype g_dtype, int64_t n,
+                                    const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag,
+                                    const float *grad_scale_dev, hipStream_t stream)
+{
+    const DevCtl ctl{skip_flag, grad_scale_dev};
+    if (n == 0)
+        return ZC_OK;
+    const AdamScalars s = make_scalars(hp);
+    const Tune &t = tune();
+    const bool g_bf16 = g_dtype == ZC_BF16;
+    const int64_t g_size = g_bf16 ? 2 : 4;
+    const int arith = (int)t.adam_arith;
+
+    const int64_t to_line = (32 - e0 % 32) % 32, to_vec = (4 - e0 % 4) % 4;
+    auto vec_ok_after = [&](int64_t k) {
+        const char *gk = static_cast<const char *>(g) + k * g_size;
+        return k < n && (e0 + k) % 4 == 0 && aligned_to(gk, g_bf16 ? 8 : 16) &&
+               (!bf16_out || aligned_to(bf16_out + k, 8));
+    };
+    int64_t peel = -1;                     // -1: the whole stretch takes the scalar kernel
+    if (n >= 4096 && vec_ok_after(to_line))
+        peel = to_line;
+    else if (vec_ok_after(to_vec))
+        peel = to_vec;
+    if (arith != 2)
+        peel = -1;                         // the vector kernel is built for the default arithmetic only
+
+    int cus = 0;
+    if (peel != 0)
+        ZC_TRY(num_cus(&cus));
+    if (peel < 0) {
+        launch_scalar(state, state, state, state, state, state, g, g_bf16, n, bf16_out, s, ctl, arith, cus,
+                      stream, e0);
+    } else {
+        if (peel > 0) {
+            launch_scalar(state, state, state, state, state, state, g, g_bf16, peel, bf16_out, s, ctl, arith,
+                          cus, stream, e0);
+            e0 += peel;
+            g = static_cast<const char *>(g) + peel * g_size;
+            if (bf16_out)
+                bf16_out += peel;
+            n -= peel;
+        }
+        const int64_t nvec = n >> 2;
+        int64_t ntiles = (nvec + 63) / 64;
+        if (ntiles == 0)
+            ntiles = 1;  // workgroup 0 also owns the n % 4 tail
+        int cap = (int)t.adam_waves_per_cu;
+        if (cap < 0)
+            cap = g_bf16 ? 13 : 12;   // as for three arrays: measured best at every size
+        size_t lds = 0;
+        ZC_TRY(occupancy_cap_lds(cap, 64, &lds));
+        const int64_t kMaxGrid = t.launch_max_grid;
+        for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
+            const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
+            if (g_bf16)
+                hipLaunchKernelGGL((adam_vec_kernel<1, 64, true, 4, 2, true>), dim3((unsigned)count), dim3(64),
+                                   lds, stream, state, state, state, state, state, state, g, bf16_out, n, tile0,
+                                   s, ctl, e0);
+            else
+                hipLaunchKernelGGL((adam_vec_kernel<1, 64, false, 4, 2, true>), dim3((unsigned)count), dim3(64),
+                                   lds, stream, state, state, state, state, state, state, g, bf16_out, n, tile0,
+                                   s, ctl, e0);
+        }
+    }
+    ZC_HIP(hipGetLastError());
+    return ZC_OK;
+}
+
 }  // namespace zc
 
 namespace zc {
@@ -547,6 +682,64 @@ static zc_status check_adam_args(float *p, float *m, float *v, const void *g, zc
         for (int b = a + 1; b < 5; ++b)
             if (spans[a].lo < spans[b].hi && spans[b].lo < spans[a].hi)
                 return fail(ZC_ERR_INVALID_ARG, "p, m, v, g, bf16_out must not overlap");
+    return ZC_OK;
+}
+
+static zc_status check_packed_args(float *state, const void *g, zc_dtype g_dtype, int64_t n,
+                                   const zc_adam_hparams *hp, uint16_t *bf16_out, const int32_t *skip_flag)
+{
+    if (n < 0)
+        return fail(ZC_ERR_INVALID_ARG, "n is negative (%lld)", (long long)n);
+    if (n > kMaxElements)
+        return fail(ZC_ERR_UNSUPPORTED, "n exceeds 2^40 elements");
+    ZC_TRY(check_dtype(g_dtype));
+    ZC_TRY(check_hparams(hp));
+    if (n == 0)
+        return ZC_OK;
+    if (!state || !g)
+        return fail(ZC_ERR_INVALID_ARG, "state and g must not be NULL when n > 0");
+    if (!aligned_to(state, 128))
+        return fail(ZC_ERR_ALIGNMENT, "state must be 128-byte aligned");
+    if (!aligned_to(g, g_dtype == ZC_BF16 ? 2 : 4))
+        return fail(ZC_ERR_ALIGNMENT, "g is not aligned to its element size");
+    if (bf16_out && !aligned_to(bf16_out, 2))
+        return fail(ZC_ERR_ALIGNMENT, "bf16_out must be 2-byte aligned");
+    if (skip_flag && !aligned_to(skip_flag, 4))
+        return fail(ZC_ERR_ALIGNMENT, "skip_flag must be 4-byte aligned");
+    struct Span { uintptr_t lo, hi; };
+    const uintptr_t ng = (uintptr_t)n * (g_dtype == ZC_BF16 ? 2 : 4);
+    const Span spans[3] = {{(uintptr_t)state, (uintptr_t)state + (uintptr_t)zc_packed_state_numel(n) * 4},
+                           {(uintptr_t)g, (uintptr_t)g + ng},
+                           {(uintptr_t)bf16_out, (uintptr_t)bf16_out + (bf16_out ? (uintptr_t)n * 2 : 0)}};
+    for (int a = 0; a < 3; ++a)
+        for (int b = a + 1; b < 3; ++b)
+            if (spans[a].lo < spans[b].hi && spans[b].lo < spans[a].hi)
+                return fail(ZC_ERR_INVALID_ARG, "state, g, bf16_out must not overlap");
+    return ZC_OK;
+}
+
+// Per-range hyper-parameters: sorted, disjoint, inside [0, n), finite values.
+static zc_status check_ranges(const zc_adam_hparams *hp, const zc_param_range *ranges, int64_t nranges,
+                              int64_t n, const float *grad_scale_dev)
+{
+    if (nranges < 0 || (nranges > 0 && !ranges))
+        return fail(ZC_ERR_INVALID_ARG, "nranges is negative or ranges is NULL");
+    if (grad_scale_dev && !aligned_to(grad_scale_dev, 4))
+        return fail(ZC_ERR_ALIGNMENT, "grad_scale_dev must be 4-byte aligned");
+    int64_t prev_end = 0;
+    for (int64_t r = 0; r < nranges; ++r) {
+        const zc_param_range &k = ranges[r];
+        if (k.begin < prev_end || k.end < k.begin || k.end > n)
+            return fail(ZC_ERR_INVALID_ARG, "range %lld: [%lld, %lld) is out of order or outside [0, n)",
+                        (long long)r, (long long)k.begin, (long long)k.end);
+        if (!(k.lr_scale == k.lr_scale) || k.lr_scale - k.lr_scale != 0.0f ||
+            !(k.weight_decay == k.weight_decay) || k.weight_decay - k.weight_decay != 0.0f)
+            return fail(ZC_ERR_INVALID_ARG, "range %lld: lr_scale and weight_decay must be finite", (long long)r);
+        const float lr_here = hp->lr * k.lr_scale;
+        if (lr_here - lr_here != 0.0f)
+            return fail(ZC_ERR_INVALID_ARG, "range %lld: lr * lr_scale is not finite", (long long)r);
+        prev_end = k.end;
+    }
     return ZC_OK;
 }
 
@@ -587,24 +780,7 @@ extern "C" zc_status zc_adam_step_groups(float *p, float *m, float *v, const voi
 {
     using namespace zc;
     ZC_TRY(check_adam_args(p, m, v, g, g_dtype, n, hp, bf16_out, skip_flag));
-    if (nranges < 0 || (nranges > 0 && !ranges))
-        return fail(ZC_ERR_INVALID_ARG, "nranges is negative or ranges is NULL");
-    if (grad_scale_dev && !aligned_to(grad_scale_dev, 4))
-        return fail(ZC_ERR_ALIGNMENT, "grad_scale_dev must be 4-byte aligned");
-    int64_t prev_end = 0;
-    for (int64_t r = 0; r < nranges; ++r) {
-        const zc_param_range &k = ranges[r];
-        if (k.begin < prev_end || k.end < k.begin || k.end > n)
-            return fail(ZC_ERR_INVALID_ARG, "range %lld: [%lld, %lld) is out of order or outside [0, n)",
-                        (long long)r, (long long)k.begin, (long long)k.end);
-        if (!(k.lr_scale == k.lr_scale) || k.lr_scale - k.lr_scale != 0.0f ||
-            !(k.weight_decay == k.weight_decay) || k.weight_decay - k.weight_decay != 0.0f)
-            return fail(ZC_ERR_INVALID_ARG, "range %lld: lr_scale and weight_decay must be finite", (long long)r);
-        const float lr_here = hp->lr * k.lr_scale;
-        if (lr_here - lr_here != 0.0f)
-            return fail(ZC_ERR_INVALID_ARG, "range %lld: lr * lr_scale is not finite", (long long)r);
-        prev_end = k.end;
-    }
+    ZC_TRY(check_ranges(hp, ranges, nranges, n, grad_scale_dev));
     if (n == 0)
         return ZC_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -616,6 +792,44 @@ extern "C" zc_status zc_adam_step_groups(float *p, float *m, float *v, const voi
         return launch_adam(p + begin, m + begin, v + begin, static_cast<const char *>(g) + begin * g_size,
                            g_dtype, end - begin, &h, bf16_out ? bf16_out + begin : nullptr, skip_flag, stream,
                            -1, grad_scale_dev);
+    };
+    int64_t at = 0;
+    for (int64_t r = 0; r < nranges; ++r) {
+        ZC_TRY(launch(at, ranges[r].begin, *hp));
+        zc_adam_hparams h = *hp;
+        h.lr = hp->lr * ranges[r].lr_scale;  // one fp32 product
+        h.weight_decay = ranges[r].weight_decay;
+        ZC_TRY(launch(ranges[r].begin, ranges[r].end, h));
+        at = ranges[r].end;
+    }
+    return launch(at, n, *hp);
+}
+
+extern "C" int64_t zc_packed_state_numel(int64_t n)
+{
+    if (n <= 0)
+        return 0;
+    return 3 * ((n + zc::kGranule - 1) / zc::kGranule) * zc::kGranule;
+}
+
+extern "C" zc_status zc_adam_step_packed(float *state, const void *g, zc_dtype g_dtype, int64_t n,
+                                         const zc_adam_hparams *hp, const zc_param_range *ranges,
+                                         int64_t nranges, uint16_t *bf16_out, const int32_t *skip_flag,
+                                         const float *grad_scale_dev, void *hip_stream)
+{
+    using namespace zc;
+    ZC_TRY(check_packed_args(state, g, g_dtype, n, hp, bf16_out, skip_flag));
+    ZC_TRY(check_ranges(hp, ranges, nranges, n, grad_scale_dev));
+    if (n == 0)
+        return ZC_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t g_size = g_dtype == ZC_BF16 ? 2 : 4;
+    auto launch = [&](int64_t begin, int64_t end, const zc_adam_hparams &h) -> zc_status {
+        if (end <= begin)
+            return ZC_OK;
+        return launch_adam_packed(state, begin, static_cast<const char *>(g) + begin * g_size, g_dtype,
+                                  end - begin, &h, bf16_out ? bf16_out + begin : nullptr, skip_flag,
+                                  grad_scale_dev, stream);
     };
     int64_t at = 0;
     for (int64_t r = 0; r < nranges; ++r) {

@@ -1,6 +1,7 @@
 """Launch-shape and placement sweeps for libzc on the GPU at hand.
 
     python -m paper_2504_09983_amd.tune adam      [--workload llama3_8b|llama3_70b|mixtral_8x7b] [--grid coarse|fine|nt]
+    python -m paper_2504_09983_amd.tune packed    [--workload ...]  the same update over the packed state array, by wave cap
     python -m paper_2504_09983_amd.tune streams   norm, cast, accumulate and unshard: resident-wave caps, grid, unroll
     python -m paper_2504_09983_amd.tune placement how far apart p, m, v, g and the bf16 copy sit in memory
     python -m paper_2504_09983_amd.tune link      host link: one direction, both, 2:1 mix, zero-copy launch shapes,
@@ -94,6 +95,57 @@ def sweep_adam(args):
             zc.tune_set(k, val)
         cells = [f"{_frac(bpe * n, _timeit(torch, fn, reps)):.3f}" for bpe, fn in variants.values()]
         print(f"{b:5d} {r:4d} {w:5d} {nt:2d} | " + " | ".join(cells), flush=True)
+
+
+def sweep_packed(args):
+    """The update over the packed state array (zc_adam_step_packed) next to the three-array
+    update on the same GPU in the same process, by resident-wave cap."""
+    torch, synth, zc = _setup()
+    dev = "cuda:0"
+    _, n, _ = zc.flat_layout(synth.tensor_numels(synth.SHAPES[args.workload]), 8, 1)
+    reps = args.reps or (10 if n < (1 << 31) else 4)
+    g = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    synth.device_normal_(g, synth.G_STD, seed=2001)
+    g32 = torch.empty(n, dtype=torch.float32, device=dev)
+    synth.device_normal_(g32, synth.G_STD, seed=2002)
+    out = torch.empty(n, dtype=torch.int16, device=dev)
+    hp = zc.hparams(step=3, **synth.HP)
+    print(f"# {args.workload} n={n} reps={reps}; columns: fraction of 8 TB/s per variant", flush=True)
+    print("# layout waves | bf16 g + copy (28 B) | bf16 g (26 B) | fp32 g + copy (30 B) | fp32 g (28 B)", flush=True)
+    for layout in ("packed", "arrays"):
+        if layout == "packed":
+            state = torch.empty(zc.packed_state_numel(n), dtype=torch.float32, device=dev)
+            cube = state.view(-1, 3, zc.PACKED_GRANULE)
+            for k in range(0, cube.shape[0], 1 << 12):
+                rows = min(1 << 12, cube.shape[0] - k)
+                cube[k:k + rows, 0] = torch.randn(rows, zc.PACKED_GRANULE, device=dev) * synth.P_STD
+            cube[:, 1:].zero_()
+
+            def upd(grad, dt, **kw):
+                zc.adam_step_packed(state, grad, dt, n, hp, **kw)
+        else:
+            p = torch.empty(n, dtype=torch.float32, device=dev)
+            synth.device_normal_(p, synth.P_STD, seed=2)
+            m = torch.zeros(n, dtype=torch.float32, device=dev)
+            v = torch.zeros(n, dtype=torch.float32, device=dev)
+
+            def upd(grad, dt, **kw):
+                zc.adam_step(p, m, v, grad, dt, n, hp, **kw)
+        variants = [(28, lambda: upd(g, zc.BF16, bf16_out=out)), (26, lambda: upd(g, zc.BF16)),
+                    (30, lambda: upd(g32, zc.F32, bf16_out=out)), (28, lambda: upd(g32, zc.F32))]
+        for _, fn in variants:
+            fn()
+        torch.cuda.synchronize()
+        for w in (-1, 9, 10, 11, 12, 13, 14, 15, 16):
+            zc.tune_set("adam.waves_per_cu", w)
+            cells = [f"{_frac(bpe * n, _timeit(torch, fn, reps)):.3f}" for bpe, fn in variants]
+            print(f"{layout:7s} {'default' if w < 0 else w:>7} | " + " | ".join(cells), flush=True)
+        zc.tune_set("adam.waves_per_cu", -1)
+        if layout == "packed":
+            del state, cube
+        else:
+            del p, m, v
+        torch.cuda.empty_cache()
 
 
 def sweep_streams(args):
@@ -330,6 +382,10 @@ def main():
     a.add_argument("--grid", default="fine", choices=["coarse", "fine", "nt"])
     a.add_argument("--reps", type=int, default=0)
     a.set_defaults(fn=sweep_adam)
+    k = sub.add_parser("packed")
+    k.add_argument("--workload", default="llama3_8b", choices=["llama3_8b", "llama3_70b", "mixtral_8x7b"])
+    k.add_argument("--reps", type=int, default=0)
+    k.set_defaults(fn=sweep_packed)
     sub.add_parser("streams").set_defaults(fn=sweep_streams)
     sub.add_parser("placement").set_defaults(fn=sweep_placement)
     l = sub.add_parser("link")

@@ -85,6 +85,15 @@ def lib():
     L.zc_adam_step_groups.restype = ctypes.c_int
     L.zc_adam_step_groups.argtypes = [vp, vp, vp, vp, ctypes.c_int, i64, ctypes.POINTER(AdamHparams),
                                       ctypes.POINTER(ParamRange), i64, vp, vp, vp, vp]
+    L.zc_packed_state_numel.restype = i64
+    L.zc_packed_state_numel.argtypes = [i64]
+    L.zc_state_pack.restype = ctypes.c_int
+    L.zc_state_pack.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.zc_state_unpack.restype = ctypes.c_int
+    L.zc_state_unpack.argtypes = [vp, i64, vp, vp, vp, vp]
+    L.zc_adam_step_packed.restype = ctypes.c_int
+    L.zc_adam_step_packed.argtypes = [vp, vp, ctypes.c_int, i64, ctypes.POINTER(AdamHparams),
+                                      ctypes.POINTER(ParamRange), i64, vp, vp, vp, vp]
     L.zc_clip_scale.restype = ctypes.c_int
     L.zc_clip_scale.argtypes = [vp, ctypes.c_float, ctypes.c_float, vp, vp]
     L.zc_cast_bf16.restype = ctypes.c_int
@@ -196,6 +205,31 @@ def adam_step_groups(p, m, v, g, g_dtype: int, n: int, hp: AdamHparams, ranges=(
     _check(lib().zc_adam_step_groups(_addr(p), _addr(m), _addr(v), _addr(g), g_dtype, n,
                                      ctypes.byref(hp), arr, len(ranges), _addr(bf16_out),
                                      _addr(skip_flag), _addr(grad_scale_dev), _stream(stream)))
+
+
+PACKED_GRANULE = 8192
+
+
+def packed_state_numel(n: int) -> int:
+    return int(lib().zc_packed_state_numel(n))
+
+
+def state_pack(p, m, v, n: int, state, stream=None) -> None:
+    _check(lib().zc_state_pack(_addr(p), _addr(m), _addr(v), n, _addr(state), _stream(stream)))
+
+
+def state_unpack(state, n: int, p=None, m=None, v=None, stream=None) -> None:
+    _check(lib().zc_state_unpack(_addr(state), n, _addr(p), _addr(m), _addr(v), _stream(stream)))
+
+
+def adam_step_packed(state, g, g_dtype: int, n: int, hp: AdamHparams, ranges=(), bf16_out=None,
+                     skip_flag=None, grad_scale_dev=None, stream=None) -> None:
+    """ranges = [(begin, end, lr_scale, weight_decay), ...]"""
+    arr = (ParamRange * max(1, len(ranges)))(*[ParamRange(int(b), int(e), float(s), float(w))
+                                               for b, e, s, w in ranges])
+    _check(lib().zc_adam_step_packed(_addr(state), _addr(g), g_dtype, n, ctypes.byref(hp), arr,
+                                     len(ranges), _addr(bf16_out), _addr(skip_flag),
+                                     _addr(grad_scale_dev), _stream(stream)))
 
 
 def clip_scale(sqnorm, max_norm: float, inv_loss_scale: float, scale_out, stream=None) -> None:

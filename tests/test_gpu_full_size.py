@@ -87,6 +87,60 @@ def test_llama70b_shard_step_and_cast():
     torch.cuda.empty_cache()
 
 
+def packed_positions(s, w, granule):
+    """Positions of p[s : s + w] in the packed state array, from the layout's definition
+    (granule k of p, m, v follow each other); m sits one granule and v two granules behind."""
+    e = np.arange(s, s + w, dtype=np.int64)
+    return (e // granule) * 3 * granule + e % granule
+
+
+def test_llama70b_shard_packed_state_ten_steps():
+    """The same 70B shard held as one packed state array (the layout the benchmark's headline
+    times): 10 steps with the fused bf16 copy, the oracle following on windows that are read
+    out of the packed array by the layout's definition."""
+    G = zc.PACKED_GRANULE
+    _, n, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_70B), 8, 1)
+    steps = 10
+    state = torch.empty(zc.packed_state_numel(n), dtype=torch.float32, device=DEV)
+    cube = state.view(-1, 3, G)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(11)
+    for k in range(0, cube.shape[0], 1 << 12):                 # 2^25 elements of p per draw
+        rows = min(1 << 12, cube.shape[0] - k)
+        cube[k:k + rows, 0] = torch.randn(rows, G, generator=gen, device=DEV) * synth.P_STD
+    cube[:, 1:].zero_()
+    g = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(n, dtype=torch.int16, device=DEV)
+    wins = windows_for(n, extra_boundaries=[n // 2, 5 * G, (n // G) * G], seed=5)
+    where = [torch.from_numpy(packed_positions(s, w, G)).to(DEV) for s, w in wins]
+    host = [(host_f32(state[at]).copy(), np.zeros(w, np.float32), np.zeros(w, np.float32),
+             np.zeros(w, np.uint16)) for (s, w), at in zip(wins, where)]
+    for t in range(1, steps + 1):
+        synth.device_normal_(g, synth.G_STD, seed=3000 + t)
+        zc.adam_step_packed(state, g, zc.BF16, n, zc.hparams(step=t, **HP), bf16_out=out)
+        sync()
+        for (s, w), (hp_, hm_, hv_, ho_) in zip(wins, host):
+            oracle.adam_step(hp_, hm_, hv_, host_u16(g[s:s + w]), step=t, bf16_out=ho_, **HP)
+        print(f"step {t} done", flush=True)
+    for (s, w), at, (hp_, hm_, hv_, ho_) in zip(wins, where, host):
+        gp, gm, gv = host_f32(state[at]), host_f32(state[at + G]), host_f32(state[at + 2 * G])
+        assert_state_close(gp, gm, gv, hp_, hm_, hv_, steps=steps, tag=f"packed window@{s}")
+        assert np.array_equal(host_u16(out[s:s + w]), oracle.cast_bf16(gp)), f"window@{s}: fused cast"
+    # at full size: the bf16 copy is torch's RNE narrowing of the p granules, every 8th chunk
+    rows = 1 << 15                                              # 2^28 elements per chunk
+    for k in range(0, cube.shape[0], rows * 8):
+        k1 = min(cube.shape[0], k + rows)
+        e = min(n, k1 * G)
+        pk = cube[k:k1, 0].reshape(-1)[:e - k * G]
+        assert torch.equal(pk.to(torch.bfloat16).view(torch.int16), out[k * G:e]), f"chunk@{k * G}"
+        del pk
+    whole = 3 * (n // G) * G                                    # the last granule's padding is never touched
+    for s0 in range(0, whole, 1 << 30):
+        assert torch.isfinite(state[s0:min(whole, s0 + (1 << 30))]).all(), f"state chunk@{s0}"
+    del state, cube, g, out
+    torch.cuda.empty_cache()
+
+
 def test_llama70b_shard_every_element_after_step_one():
     """Step 1 from m = v = 0 has a closed form in every element: m = (1-b1) g, v = (1-b2) g^2,
     p = p0 (1 - lr wd) - lr g / (|g| + eps) up to rounding.  Checked over all 8.8 B elements with

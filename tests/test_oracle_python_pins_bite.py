@@ -9,6 +9,7 @@ import pytest
 
 from oracle import layout, planner
 from tests import test_oracle_cast_unshard as U
+from tests import test_oracle_packed_state as K
 from tests import test_oracle_planner as T
 
 PLANNER_MUTATIONS = {
@@ -73,6 +74,18 @@ LAYOUT_MUTATIONS = {
                                              "                segs.append((t, r * L + o, 0, k))"),
     "segment_source_ignores_the_tensor_offset": ("                segs.append((t, r * L + o, r * s, k))",
                                                  "                segs.append((t, r * L, r * s, k))"),
+    # packed optimizer state
+    "packed_length_rounded_down": ("    return 3 * (-(-int(n) // granule)) * granule", "    return 3 * (int(n) // granule) * granule"),
+    "packed_length_without_padding": ("    return 3 * (-(-int(n) // granule)) * granule", "    return 3 * int(n)"),
+    "packed_granules_two_apart": ("        base = 3 * k * granule", "        base = 2 * k * granule"),
+    "packed_momentum_and_variance_swapped": ("        out[base + granule:base + granule + (hi - lo)] = m[lo:hi]\n        out[base + 2 * granule:base + 2 * granule + (hi - lo)] = v[lo:hi]",
+                                             "        out[base + granule:base + granule + (hi - lo)] = v[lo:hi]\n        out[base + 2 * granule:base + 2 * granule + (hi - lo)] = m[lo:hi]"),
+    "packed_last_granule_dropped": ("    while k * granule < n:\n        lo, hi", "    while (k + 1) * granule <= n:\n        lo, hi"),
+    "unpack_reads_the_parameter_slot_twice": ("        m[first:first + count] = state[start + granule:start + granule + count]",
+                                              "        m[first:first + count] = state[start:start + count]"),
+    "unpack_granules_two_apart": ("        start = 3 * k * granule", "        start = 2 * k * granule"),
+    "unpack_short_granule_read_whole": ("first, count = k * granule, min(granule, n - k * granule)",
+                                        "first, count = k * granule, granule"),
 }
 
 PLANNER_PINS = [
@@ -93,6 +106,9 @@ LAYOUT_PINS = [
     *[(lambda n=n, a=a: U.test_per_tensor_round_trip_and_ownership(n, a)) for a in (1, 8)
       for n in ([1, 3, 7, 4097], [16, 64, 8], [5], [0, 9, 0, 2], [1000, 24, 333])],
     U.test_per_tensor_divisible_case_is_a_reshape, U.test_model_shapes_match_paper_sizes,
+    K.test_hand_worked_example, K.test_whole_granules_are_a_reshape, K.test_empty_and_rejected_inputs,
+    *[(lambda n=n, g=g: K.test_index_formula_element_by_element(n, g))
+      for n, g in ((1, 8), (7, 8), (9, 8), (37, 5), (64, 8))],
 ]
 
 
