@@ -240,3 +240,42 @@ def test_argument_errors():
     zc.state_pack(None, None, None, 0, None)
     zc.state_unpack(None, 0)
     sync()
+
+
+def test_packed_step_replays_from_a_hip_graph():
+    """grad-norm (the entry point that never allocates) -> packed step with skip flag and fused
+    copy, captured once and replayed: every replay equals the same calls made eagerly on a copy."""
+    n = 5 * G + 1237
+    p = synth.host_params(n, 8)
+    state = dev_state(n)
+    zc.state_pack(dev_f32(p), None, None, n, state)
+    dg = dev_u16(oracle.cast_bf16(synth.host_grads_f32(n, 6)))
+    send = torch.zeros(n, dtype=torch.int16, device=DEV)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    hp = zc.hparams(step=2, **HP)
+
+    def step(st, snd):
+        zc.grad_sqnorm_static(dg, zc.BF16, n, norm, flag)
+        zc.adam_step_packed(st, dg, zc.BF16, n, hp, ranges=[(G - 5, 2 * G + 3, 0.5, 0.0)], bf16_out=snd,
+                            skip_flag=flag)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(state.clone(), torch.zeros_like(send))   # first use looks up the static buffer's address
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(state, send)
+    sync()
+    for replay in range(4):
+        ref = state.clone()
+        ref_send = torch.zeros_like(send)
+        graph.replay()
+        sync()
+        step(ref, ref_send)
+        sync()
+        assert torch.equal(state.view(torch.int32), ref.view(torch.int32)), f"replay {replay}"
+        assert torch.equal(send, ref_send)
+        _ = (ref * 2).sum().item()                 # unrelated eager work and a sync between replays
