@@ -94,12 +94,14 @@ def packed_positions(s, w, granule):
     return (e // granule) * 3 * granule + e % granule
 
 
-def test_llama70b_shard_packed_state_ten_steps():
-    """The same 70B shard held as one packed state array (the layout the benchmark's headline
+@pytest.mark.parametrize("shape", ["LLAMA3_8B", "LLAMA3_70B"])
+def test_shard_in_packed_state_ten_steps(shape):
+    """The 8B and 70B shards held as one packed state array (the layout the benchmark's headline
     times): 10 steps with the fused bf16 copy, the oracle following on windows that are read
     out of the packed array by the layout's definition."""
     G = zc.PACKED_GRANULE
-    _, n, _ = zc.flat_layout(synth.tensor_numels(synth.LLAMA3_70B), 8, 1)
+    _, n, _ = zc.flat_layout(synth.tensor_numels(getattr(synth, shape)), 8, 1)
+    assert n == {"LLAMA3_8B": 1_003_782_656, "LLAMA3_70B": 8_819_213_312}[shape]
     steps = 10
     state = torch.empty(zc.packed_state_numel(n), dtype=torch.float32, device=DEV)
     cube = state.view(-1, 3, G)

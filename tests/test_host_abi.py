@@ -91,6 +91,52 @@ def test_adam_step_rejects_bad_arguments_without_a_gpu():
     assert _status(zc.clip_scale, A + 2, 1.0, 1.0, A + 4, stream=0) == zc.ERR_ALIGNMENT
 
 
+def test_packed_state_entry_points_reject_bad_arguments_without_a_gpu():
+    hp = zc.hparams(step=1, **HP)
+    G = zc.PACKED_GRANULE
+    assert G == 8192
+    for n in (-5, 0, 1, G - 1, G, G + 1, 7 * G + 3, 8_819_213_312):
+        assert zc.packed_state_numel(n) == olayout.packed_state_numel(n, G)
+    A = 0x400000                                  # fake, never dereferenced: validation fails first
+    far = A + 4 * zc.packed_state_numel(8) + 4096
+    ok = (A, far, zc.F32, 8, hp)
+    assert _status(zc.adam_step_packed, A, far, zc.F32, -1, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step_packed, 0, far, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step_packed, A, 0, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step_packed, A + 64, far, zc.F32, 8, hp, stream=0) == zc.ERR_ALIGNMENT      # state off a 128-byte line
+    assert _status(zc.adam_step_packed, A, far + 2, zc.F32, 8, hp, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.adam_step_packed, *ok, bf16_out=far + 4097, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.adam_step_packed, *ok, skip_flag=far + 8194, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.adam_step_packed, *ok, grad_scale_dev=far + 8193, stream=0) == zc.ERR_ALIGNMENT
+    # the whole packed array counts, padding included: g just behind element 8 of p is still inside it
+    assert _status(zc.adam_step_packed, A, A + 4 * 8, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step_packed, A, A + 4 * 3 * G - 4, zc.F32, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert "overlap" in zc.last_error()
+    assert _status(zc.adam_step_packed, *ok, bf16_out=far + 8, stream=0) == zc.ERR_INVALID_ARG        # copy inside g
+    assert _status(zc.adam_step_packed, A, far, 9, 8, hp, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.adam_step_packed, A, far, zc.F32, (1 << 40) + 1, hp, stream=0) == zc.ERR_UNSUPPORTED
+    assert _status(zc.adam_step_packed, A, far, zc.F32, 8, zc.hparams(**dict(HP, step=0)), stream=0) == zc.ERR_INVALID_ARG
+    for bad in ([(4, 2, 1.0, 0.0)], [(0, 9, 1.0, 0.0)], [(0, 4, 1.0, 0.0), (3, 6, 1.0, 0.0)],
+                [(0, 4, 1.0, float("inf"))]):
+        assert _status(zc.adam_step_packed, *ok, ranges=bad, stream=0) == zc.ERR_INVALID_ARG
+    zc.adam_step_packed(0, 0, zc.F32, 0, hp, stream=0)                                                # n == 0: no-op
+    # pack / unpack
+    src = far + (1 << 20)
+    assert _status(zc.state_pack, src, None, None, -1, A, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.state_pack, src, None, None, 8, 0, stream=0) == zc.ERR_INVALID_ARG
+    assert _status(zc.state_pack, src, None, None, 8, A + 16, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.state_pack, src + 2, None, None, 8, A, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.state_pack, A + 4 * G, None, None, 8, A, stream=0) == zc.ERR_INVALID_ARG          # source inside the array
+    assert _status(zc.state_pack, src, src + 16, None, 8, A, stream=0) == zc.ERR_INVALID_ARG           # sources overlap
+    assert _status(zc.state_pack, src, None, None, (1 << 40) + 1, A, stream=0) == zc.ERR_UNSUPPORTED
+    assert _status(zc.state_unpack, A, 8, src, None, src + 8, stream=0) == zc.ERR_INVALID_ARG          # p and v overlap
+    assert _status(zc.state_unpack, A + 4, 8, src, stream=0) == zc.ERR_ALIGNMENT
+    assert _status(zc.state_unpack, 0, 8, src, stream=0) == zc.ERR_INVALID_ARG
+    zc.state_pack(0, 0, 0, 0, 0, stream=0)
+    zc.state_unpack(0, 0, stream=0)
+    zc.state_unpack(A, 8, stream=0)                                                                   # nothing asked for
+
+
 def test_cast_and_sqnorm_reject_bad_arguments_without_a_gpu():
     A = 0x20000
     assert _status(zc.cast_bf16, A, A + 4096, -5, stream=0) == zc.ERR_INVALID_ARG
