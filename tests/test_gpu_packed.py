@@ -279,3 +279,86 @@ def test_packed_step_replays_from_a_hip_graph():
         assert torch.equal(state.view(torch.int32), ref.view(torch.int32)), f"replay {replay}"
         assert torch.equal(send, ref_send)
         _ = (ref * 2).sum().item()                 # unrelated eager work and a sync between replays
+
+
+PAD = 40      # guard elements around g and the bf16 copy
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_packed_step_random_case(seed):
+    """Seeded random sizes, hyper-parameters, ranges, device-side scale, both gradient types and
+    decay modes, g and the copy each at its own element offset: against the oracle, with guard
+    elements around the flat arrays and the packed array's padding watched."""
+    rng = np.random.default_rng(9000 + seed)
+    n = int(rng.choice([1, 3, 31, 33, 4095, 4097, G - 1, G, G + 1, 2 * G + 5, 3 * G - 4, 40_011, 150_003]))
+    if seed % 3 == 0:
+        n = int(rng.integers(1, 6 * G))
+    g_bf16 = bool(rng.integers(0, 2))
+    mode = int(rng.integers(0, 2))
+    with_out = bool(rng.integers(0, 2))
+    steps = int(rng.integers(1, 4))
+    hp = dict(lr=float(10.0 ** rng.uniform(-5, -2)), beta1=float(rng.choice([0.0, 0.8, 0.9, 0.95])),
+              beta2=float(rng.choice([0.9, 0.98, 0.999])), eps=float(rng.choice([1e-8, 1e-6, 1e-10])),
+              weight_decay=float(rng.choice([0.0, 0.01, 0.1])))
+    grad_scale = float(rng.choice([1.0, 0.5, 1.0 / 1024, 3.0]))
+    dev_scale = None if rng.integers(0, 2) else np.float32(rng.choice([1.0, 0.25, 0.7071]))
+    g_off, o_off = (int(x) for x in rng.integers(0, PAD, 2))
+    if rng.integers(0, 2):
+        g_off = o_off = 4 * int(rng.integers(0, PAD // 4))          # keep the wide path reachable
+    ranges = []
+    if rng.integers(0, 2) and n >= 8:
+        cuts = sorted(set(int(x) for x in rng.integers(0, n + 1, 6)))
+        for b, e in zip(cuts[0::2], cuts[1::2]):
+            ranges.append((b, e, float(rng.choice([1.0, 0.5, 2.0])), float(rng.choice([0.0, 0.05]))))
+    case = (f"seed={seed} n={n} bf16={g_bf16} mode={mode} out={with_out} steps={steps} hp={hp} gs={grad_scale} "
+            f"ds={dev_scale} g_off={g_off} o_off={o_off} ranges={ranges}")
+
+    p = synth.host_params(n, 9100 + seed)
+    m = (synth.host_grads_f32(n, 9200 + seed) * np.float32(0.1)).astype(np.float32)
+    v = (synth.host_grads_f32(n, 9300 + seed) ** 2).astype(np.float32)
+    out = np.zeros(n, np.uint16)
+    packed0 = layout.pack_state(p, m, v, G)
+    pad = np.ones(packed0.size, dtype=bool)
+    for k in range(-(-n // G)):
+        cnt = min(G, n - k * G)
+        for a in range(3):
+            pad[3 * k * G + a * G:3 * k * G + a * G + cnt] = False
+    packed0.view(np.uint32)[pad] = 0x7FC0DEAD
+    state = dev_state(n)
+    state.copy_(dev_f32(packed0))
+    out_full = torch.full((n + 2 * PAD,), 0x5EED, dtype=torch.int16, device=DEV)
+    dout = out_full[o_off:o_off + n]
+    scale_dev = None if dev_scale is None else torch.full((1,), float(dev_scale), dtype=torch.float32, device=DEV)
+    t0 = int(rng.integers(1, 2000))
+    for t in range(t0, t0 + steps):
+        g = synth.host_grads_f32(n, 9400 + 10 * seed + t % 10)
+        if g_bf16:
+            g = oracle.cast_bf16(g)
+            g_full = torch.full((n + 2 * PAD,), 0x5EED, dtype=torch.int16, device=DEV)
+            dg = g_full[g_off:g_off + n]
+            dg.copy_(dev_u16(g))
+        else:
+            g_full = torch.full((n + 2 * PAD,), 12345.0, dtype=torch.float32, device=DEV)
+            dg = g_full[g_off:g_off + n]
+            dg.copy_(dev_f32(g))
+        zc.adam_step_packed(state, dg, zc.BF16 if g_bf16 else zc.F32, n,
+                            zc.hparams(step=t, grad_scale=grad_scale, mode=mode, **hp), ranges=ranges,
+                            bf16_out=dout if with_out else None, grad_scale_dev=scale_dev)
+        oracle.adam_step_groups(p, m, v, g, ranges=ranges, step=t, grad_scale=grad_scale, mode=mode,
+                                grad_scale_dev=dev_scale, bf16_out=out if with_out else None, **hp)
+        sync()
+    got = host_f32(state)
+    assert np.array_equal(got.view(np.uint32)[pad], packed0.view(np.uint32)[pad]), case + ": padding written"
+    got = got.copy()
+    got[pad] = 0
+    gp, gm, gv = layout.unpack_state(got, n, G)
+    m_floor = 0.1 * 1e-3 * grad_scale * (float(dev_scale) if dev_scale is not None else 1.0)
+    assert_state_close(gp, gm, gv, p, m, v, tag=case, steps=steps, lr=2.0 * hp["lr"], m_floor=max(m_floor, 1e-8))
+    fill = torch.tensor(0x5EED, dtype=torch.int16, device=DEV)
+    assert bool((out_full[:o_off] == fill).all()) and bool((out_full[o_off + n:] == fill).all()), case
+    if with_out:
+        go = host_u16(dout)
+        assert np.array_equal(go, oracle.cast_bf16(gp)), case
+        assert bf16_ulp_diff(go, out).max(initial=0) <= 1, case
+    else:
+        assert bool((dout == fill).all()), case
