@@ -14,6 +14,11 @@
 // stores with the nt and sc1 bits), so that a tile's results reach DRAM together
 // instead of whenever the cache evicts them.
 //
+// p, m and v come either as three arrays or as one packed state array in which granules
+// of 8192 elements of p, m and v follow each other (zc_adam_step_packed): the same kernel
+// with one more index computation per lane.  The resident waves then work on one contiguous
+// stretch of state instead of three that lie gigabytes apart, which measured 2-4 % faster.
+//
 // The arithmetic (paper: Adam with momentum and variance buffers in fp32 next
 // to fp32 master parameters; Experimental settings, Adaptive offloading) is
 // bias-corrected Adam with epsilon outside the square root and, in ZC_ADAMW
