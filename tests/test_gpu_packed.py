@@ -362,3 +362,16 @@ def test_packed_step_random_case(seed):
         assert bf16_ulp_diff(go, out).max(initial=0) <= 1, case
     else:
         assert bool((dout == fill).all()), case
+
+
+def test_packed_step_cut_into_several_launches():
+    """A tiny launch limit forces the multi-launch path (tile offsets) of the packed kernel, with
+    stretches that start inside a granule."""
+    old = zc.tune_get("launch.max_grid")
+    zc.tune_set("launch.max_grid", 7)
+    try:
+        n = 3 * G + 1031                      # 97 rows of 256 elements -> 14 launches
+        gpu, cpu = run_packed(n, 2, g_bf16=True, seed=3, ranges=[(300, 2 * G + 9, 0.5, 0.0)])
+        check(gpu, cpu, tag="packed cut launches", steps=2)
+    finally:
+        zc.tune_set("launch.max_grid", old)
