@@ -164,7 +164,7 @@ static const Knob *find_knob(const char *key)
 
 extern "C" {
 
-int zc_version(void) { return 200; }
+int zc_version(void) { return 20100; }   // 2.1.0: packed optimizer state
 
 const char *zc_last_error(void) { return zc::g_err; }
 

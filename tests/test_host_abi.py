@@ -33,7 +33,7 @@ def test_library_loads_and_exports_every_declared_symbol():
             "zc_schedule_run"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
-    assert zc.version() >= 100
+    assert zc.version() == 20100
 
 
 def test_hparams_struct_layout_matches_header():
