@@ -482,8 +482,8 @@ zc_status zc_grad_sqnorm_static(const void *g, zc_dtype g_dtype, int64_t n, floa
  *                      zc_grad_sqnorm: 1-16, default 2
  *   "copy.nontemporal"  cast, unshard, accumulation: 0 = ordinary accesses, 1 = non-temporal,
  *                      2 (default) = non-temporal loads and write-through streaming stores
- *   "launch.max_grid"  workgroups per launch (default 2^30); larger jobs are cut into
- *                      several launches
+ *   "launch.max_grid"  workgroups per launch (default 2^30, and never more than fit into
+ *                      2^32 - 1 threads); larger jobs are cut into several launches
  *   "offload.zero_copy" 0 = staged ring, 1 = kernel reads/writes pinned host (default),
  *                      2 = staged reads + kernel writes pinned host
  *   "offload.zc_waves_per_cu"  resident-wave cap of the zero-copy kernel (0 = none)

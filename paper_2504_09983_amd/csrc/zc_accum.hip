@@ -130,7 +130,7 @@ extern "C" zc_status zc_grad_accumulate(float *acc, const void *micro, zc_dtype 
             ntiles = 1;
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds((int)tune().accum_waves_per_cu, kAccBlock, &lds));
-        const int64_t kAccMaxGrid = tune().launch_max_grid;
+        const int64_t kAccMaxGrid = max_workgroups_per_launch(tune().launch_max_grid, kAccBlock);
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kAccMaxGrid) {
             const int64_t count = (ntiles - tile0) < kAccMaxGrid ? (ntiles - tile0) : kAccMaxGrid;
             const bool stream_out = tune().copy_nontemporal == 2;

@@ -563,7 +563,7 @@ zc_status launch_adam(float *p, float *m, float *v, const void *g, zc_dtype g_dt
             cap = g_bf16 ? 13 : 12;
         ZC_TRY(occupancy_cap_lds(cap, block, &lds));
         VecLaunch a{dim3(1), lds, stream, p, m, v, po, mo, vo, g, bf16_out, n, 0, s, ctl};
-        const int64_t kMaxGrid = t.launch_max_grid;
+        const int64_t kMaxGrid = max_workgroups_per_launch(t.launch_max_grid, block);
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             a.grid = dim3((unsigned)count);
@@ -634,7 +634,7 @@ static zc_status launch_adam_packed(float *state, int64_t e0, const void *g, zc_
             cap = g_bf16 ? 13 : 12;   // as for three arrays: measured best at every size
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds(cap, 64, &lds));
-        const int64_t kMaxGrid = t.launch_max_grid;
+        const int64_t kMaxGrid = max_workgroups_per_launch(t.launch_max_grid, 64);
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             if (g_bf16)

@@ -287,7 +287,7 @@ zc_status zc_cast_bf16(const float *src, uint16_t *dst, int64_t n, void *hip_str
             ntiles = 1;  // workgroup 0 also owns the n % 4 tail
         size_t lds = 0;
         ZC_TRY(occupancy_cap_lds((int)t.cast_waves_per_cu, kCopyBlock, &lds));
-        const int64_t kMaxGrid = t.launch_max_grid;
+        const int64_t kMaxGrid = max_workgroups_per_launch(t.launch_max_grid, kCopyBlock);
         for (int64_t tile0 = 0; tile0 < ntiles; tile0 += kMaxGrid) {
             const int64_t count = (ntiles - tile0) < kMaxGrid ? (ntiles - tile0) : kMaxGrid;
             if (t.copy_nontemporal == 2)
@@ -457,7 +457,7 @@ zc_status zc_unshard(const zc_unshard_plan *plan, const uint16_t *gathered, void
     const Tune &t = tune();
     size_t lds = 0;
     ZC_TRY(occupancy_cap_lds((int)t.copy_waves_per_cu, kCopyBlock, &lds));
-    const int64_t kMaxGrid = t.launch_max_grid;
+    const int64_t kMaxGrid = max_workgroups_per_launch(t.launch_max_grid, kCopyBlock);
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int64_t tile0 = 0; tile0 < plan->ntiles; tile0 += kMaxGrid) {
         const int64_t left = plan->ntiles - tile0;

@@ -105,6 +105,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t stream_out_rsrc(void *base, in
 }
 #endif
 
+// Workgroups one launch may have: the "launch.max_grid" knob, and never so many that the
+// launch would exceed 2^32 - 1 threads in x.  The dispatch packet counts threads in 32 bits,
+// and a larger launch does not fail: it silently runs the count modulo 2^32.
+inline int64_t max_workgroups_per_launch(int64_t knob, int block_threads)
+{
+    const int64_t hw = int64_t(0xFFFFFFFFu) / block_threads;
+    return knob < hw ? knob : hw;
+}
+
 inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 constexpr int64_t kMaxElements = int64_t(1) << 40;

@@ -402,3 +402,54 @@ def test_norm_cast_and_accumulation_at_the_70b_shard_size():
         assert np.array_equal(host_u16(out[s:s + w]), oracle.cast_bf16(host_f32(acc[s:s + w]))), f"cast window@{s}"
     del g, acc, out
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("state_layout", ["arrays", "packed"])
+def test_update_over_more_vectors_than_one_launch_can_count(state_layout):
+    """n = 2^34 + 2^20 + 5 elements: more 16-byte vectors than the 2^32 - 1 threads one launch can
+    have (a larger launch does not fail, it silently runs the count modulo 2^32), so the update is
+    cut into two launches.  Step 1 from m = v = 0 has a closed form in every element, checked over
+    the whole partition in chunks: an element no launch reached would keep m = 0.  240 GB resident."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    G = zc.PACKED_GRANULE
+    n = (1 << 34) + (1 << 20) + 5
+    b1, b2 = float(np.float32(HP["beta1"])), float(np.float32(HP["beta2"]))
+    g = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    synth.device_normal_(g, synth.G_STD, seed=4001)
+    if state_layout == "packed":
+        state = torch.empty(zc.packed_state_numel(n), dtype=torch.float32, device=DEV)
+        cube = state.view(-1, 3, G)
+        cube[:, 0].fill_(0.25)
+        cube[:, 1:].zero_()
+        zc.adam_step_packed(state, g, zc.BF16, n, zc.hparams(step=1, **HP))
+    else:
+        p = torch.full((n,), 0.25, dtype=torch.float32, device=DEV)
+        m = torch.zeros(n, dtype=torch.float32, device=DEV)
+        v = torch.zeros(n, dtype=torch.float32, device=DEV)
+        zc.adam_step(p, m, v, g, zc.BF16, n, zc.hparams(step=1, **HP))
+    sync()
+    print("step done", flush=True)
+    rows = 1 << 14                                              # 2^27 elements per chunk
+    for k in range(0, -(-n // G), rows):
+        s, e = k * G, min(n, (k + rows) * G)
+        gd = g[s:e].double()
+        if state_layout == "packed":
+            k1 = min(cube.shape[0], k + rows)
+            pm, mm, vm = (cube[k:k1, a].reshape(-1)[:e - s] for a in range(3))
+        else:
+            pm, mm, vm = p[s:e], m[s:e], v[s:e]
+        assert torch.equal(mm, (gd * (1.0 - b1)).float()), f"m chunk@{s}"
+        assert torch.equal(vm, ((gd * (1.0 - b2)) * gd).float()), f"v chunk@{s}"
+        # p moved by the decay and by at most lr in (nearly) every element; the few whose update
+        # cancels the decay exactly are why this is not asked of all of them
+        assert float((pm != 0.25).float().mean()) > 0.999, f"p chunk@{s}"
+        assert float((pm - 0.25).abs().max()) <= 1.01e-4, f"p chunk@{s}"
+        del gd, pm, mm, vm
+    if state_layout == "packed":
+        del state, cube
+    else:
+        del p, m, v
+    del g
+    torch.cuda.empty_cache()
