@@ -18,7 +18,7 @@ __device__ __forceinline__ int64_t state_at(int64_t e)
     return e + ((e >> kStateGranuleShift) << (kStateGranuleShift + 1));
 }
 
-// Elements [lo, hi), W floats per lane (1 or 4; lo, hi and the granule are multiples of W).
+// The ragged end and misaligned arrays: elements [lo, hi), one per lane (W = 1), grid-stride.
 // PACK: state <- p, m, v, a NULL source or an element at or beyond n giving 0.
 // else: p, m, v <- state, NULL destinations skipped (hi <= n).
 template <typename T, bool PACK>
@@ -48,6 +48,52 @@ __global__ __launch_bounds__(256) void state_copy_kernel(float *state, float *p,
     }
 }
 
+// The wide path: one-wave workgroups in tile order, kStateRows 16-byte vectors per lane and
+// array, all loads of a tile issued before its stores, non-temporal both ways.  Elements
+// [0, 4 * nvec); `tile0` is the tile of workgroup 0.
+constexpr int kStateRows = 4;
+
+template <bool PACK>
+__global__ __launch_bounds__(64) void state_tile_kernel(float *state, float *p, float *m, float *v,
+                                                        int64_t nvec, int64_t tile0)
+{
+    const int64_t first = (tile0 + blockIdx.x) * (64 * kStateRows) + threadIdx.x;
+    f32x4 a[kStateRows], b[kStateRows], c[kStateRows];
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < kStateRows; ++r) {
+        const int64_t i = first + r * 64;
+        if (i < nvec) {
+            const int64_t at = state_at(i << 2);
+            if constexpr (PACK) {
+                a[r] = p ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p) + i) : zero;
+                b[r] = m ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(m) + i) : zero;
+                c[r] = v ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(v) + i) : zero;
+            } else {
+                if (p) a[r] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(state + at));
+                if (m) b[r] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(state + at + kStateGranule));
+                if (v) c[r] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(state + at + 2 * kStateGranule));
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kStateRows; ++r) {
+        const int64_t i = first + r * 64;
+        if (i < nvec) {
+            const int64_t at = state_at(i << 2);
+            if constexpr (PACK) {
+                __builtin_nontemporal_store(a[r], reinterpret_cast<f32x4 *>(state + at));
+                __builtin_nontemporal_store(b[r], reinterpret_cast<f32x4 *>(state + at + kStateGranule));
+                __builtin_nontemporal_store(c[r], reinterpret_cast<f32x4 *>(state + at + 2 * kStateGranule));
+            } else {
+                if (p) __builtin_nontemporal_store(a[r], reinterpret_cast<f32x4 *>(p) + i);
+                if (m) __builtin_nontemporal_store(b[r], reinterpret_cast<f32x4 *>(m) + i);
+                if (v) __builtin_nontemporal_store(c[r], reinterpret_cast<f32x4 *>(v) + i);
+            }
+        }
+    }
+}
+
 template <bool PACK>
 static zc_status run_state_copy(float *state, float *p, float *m, float *v, int64_t n, hipStream_t stream)
 {
@@ -63,9 +109,18 @@ static zc_status run_state_copy(float *state, float *p, float *m, float *v, int6
         const int64_t cap = (int64_t)cus * 16;
         return dim3((unsigned)(b < 1 ? 1 : (b > cap ? cap : b)));
     };
-    if (wide_end > 0)
-        hipLaunchKernelGGL((state_copy_kernel<f32x4, PACK>), blocks_for(wide_end / 4), dim3(256), 0, stream,
-                           state, p, m, v, (int64_t)0, wide_end, n);
+    if (wide_end > 0) {
+        const int64_t nvec = wide_end >> 2;
+        const int64_t ntiles = (nvec + 64 * kStateRows - 1) / (64 * kStateRows);
+        size_t lds = 0;
+        ZC_TRY(occupancy_cap_lds((int)tune().copy_waves_per_cu, 64, &lds));
+        const int64_t per_launch = max_workgroups_per_launch(tune().launch_max_grid, 64);
+        for (int64_t tile0 = 0; tile0 < ntiles; tile0 += per_launch) {
+            const int64_t count = (ntiles - tile0) < per_launch ? (ntiles - tile0) : per_launch;
+            hipLaunchKernelGGL((state_tile_kernel<PACK>), dim3((unsigned)count), dim3(64), lds, stream, state, p, m,
+                               v, nvec, tile0);
+        }
+    }
     if (end > wide_end)
         hipLaunchKernelGGL((state_copy_kernel<float, PACK>), blocks_for(end - wide_end), dim3(256), 0, stream,
                            state, p, m, v, wide_end, end, n);
