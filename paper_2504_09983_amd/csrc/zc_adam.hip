@@ -207,24 +207,6 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
     typedef stream_u32x2 u32x2v;
     constexpr int64_t kTileVecs = (int64_t)BLOCK * ROWS;
     const int64_t tile_first = first - threadIdx.x;
-    __amdgpu_buffer_rsrc_t rp, rm, rv, ro;
-    int64_t packed_first = 0;                        // packed vector index of the tile's first vector
-    if constexpr (NT == 4) {
-        int64_t vecs = nvec - tile_first;            // whole 16-byte vectors this tile may write
-        vecs = vecs < 0 ? 0 : (vecs > kTileVecs ? kTileVecs : vecs);
-        if constexpr (PACKED) {
-            packed_first = packed_vec_at(gv0 + tile_first);
-            const int64_t span = vecs > 0 ? packed_vec_at(gv0 + tile_first + vecs - 1) - packed_first + 1 : 0;
-            rp = stream_out_rsrc(po4 + packed_first, span * 16);
-            rm = stream_out_rsrc(po4 + packed_first + kGranuleVecs, span * 16);
-            rv = stream_out_rsrc(po4 + packed_first + 2 * kGranuleVecs, span * 16);
-        } else {
-            rp = stream_out_rsrc(po4 + tile_first, vecs * 16);
-            rm = stream_out_rsrc(mo4 + tile_first, vecs * 16);
-            rv = stream_out_rsrc(vo4 + tile_first, vecs * 16);
-        }
-        ro = stream_out_rsrc(out2 ? (void *)(out2 + tile_first) : (void *)po4, out2 ? vecs * 8 : 0);
-    }
     f32x4 pv[ROWS], mv[ROWS], vv[ROWS], gv[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -250,6 +232,32 @@ __device__ __forceinline__ void adam_tile(const f32x4 *p4, const f32x4 *m4, cons
                 gv[r] = ld<NTL>(reinterpret_cast<const f32x4 *>(g) + i);
             }
         }
+    }
+    // Store descriptors (mode 4) are set up after the loads have been issued: the scalar work
+    // must not stand between a wave's start and its first load (it did, ~50 instructions, when
+    // it was written first; the fence keeps the compiler from hoisting it back).
+    if constexpr (ROWS == 1)
+        __builtin_amdgcn_sched_barrier(0);
+    __amdgpu_buffer_rsrc_t rp, rm, rv, ro;
+    int64_t packed_first = 0;                        // packed vector index of the tile's first vector
+    if constexpr (NT == 4) {
+        int64_t vecs = kTileVecs;                    // whole 16-byte vectors this tile may write
+        if constexpr (GUARD) {
+            vecs = nvec - tile_first;
+            vecs = vecs < 0 ? 0 : (vecs > kTileVecs ? kTileVecs : vecs);
+        }
+        if constexpr (PACKED) {
+            packed_first = packed_vec_at(gv0 + tile_first);
+            const int64_t span = vecs > 0 ? packed_vec_at(gv0 + tile_first + vecs - 1) - packed_first + 1 : 0;
+            rp = stream_out_rsrc(po4 + packed_first, span * 16);
+            rm = stream_out_rsrc(po4 + packed_first + kGranuleVecs, span * 16);
+            rv = stream_out_rsrc(po4 + packed_first + 2 * kGranuleVecs, span * 16);
+        } else {
+            rp = stream_out_rsrc(po4 + tile_first, vecs * 16);
+            rm = stream_out_rsrc(mo4 + tile_first, vecs * 16);
+            rv = stream_out_rsrc(vo4 + tile_first, vecs * 16);
+        }
+        ro = stream_out_rsrc(out2 ? (void *)(out2 + tile_first) : (void *)po4, out2 ? vecs * 8 : 0);
     }
     if (skip_now != 0)
         return;
