@@ -1,7 +1,8 @@
 """Build libzc.so (HIP, gfx950) in-tree with hipcc.
 
 ``python -m paper_2504_09983_amd.build`` compiles every ``csrc/*.hip`` to an
-object under ``_build/`` (git-ignored) and links ``paper_2504_09983_amd/libzc.so``.
+object under ``_build/`` (git-ignored) and links ``paper_2504_09983_amd/libzc.so``, then builds
+the stand-alone measurement program ``state_layout_probe`` from ``csrc/probe/``.
 hipcc cross-compiles, so no GPU is needed to build.
 """
 from __future__ import annotations
@@ -18,6 +19,8 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libzc.so")
+PROBE_SRC = os.path.join(CSRC, "probe", "state_layout_probe.hip")
+PROBE = os.path.join(PKG, "state_layout_probe")      # stand-alone measurement program (tune.py runs it)
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
@@ -56,8 +59,15 @@ def build(jobs: int = 8, verbose: bool = True) -> str:
     cmd = [HIPCC, "-shared", "-fPIC", f"--offload-arch={ARCH}", *objs, "-o", tmp]
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    tmp = PROBE + f".tmp{os.getpid()}"
+    cmd = [HIPCC, "-O3", "-std=c++17", f"--offload-arch={ARCH}", *DEVICE_FLAGS, "-Wno-unused-command-line-argument",
+           "-Wno-unknown-warning-option", PROBE_SRC, "-o", tmp]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {PROBE_SRC}:\n{proc.stderr}")
+    os.replace(tmp, PROBE)
     if verbose:
-        print(f"built {LIB} from {len(srcs)} sources")
+        print(f"built {LIB} from {len(srcs)} sources and {PROBE}")
     return LIB
 
 

@@ -2,6 +2,8 @@
 
     python -m paper_2504_09983_amd.tune adam      [--workload llama3_8b|llama3_70b|mixtral_8x7b] [--grid coarse|fine|nt]
     python -m paper_2504_09983_amd.tune packed    [--workload ...]  the same update over the packed state array, by wave cap
+    python -m paper_2504_09983_amd.tune layout    [--elements N] [--grads bf16|fp32]  stand-alone probe: three state arrays
+                                                  against one packed array, by granule size
     python -m paper_2504_09983_amd.tune streams   norm, cast, accumulate and unshard: resident-wave caps, grid, unroll
     python -m paper_2504_09983_amd.tune placement how far apart p, m, v, g and the bf16 copy sit in memory
     python -m paper_2504_09983_amd.tune link      host link: one direction, both, 2:1 mix, zero-copy launch shapes,
@@ -146,6 +148,18 @@ def sweep_packed(args):
         else:
             del p, m, v
         torch.cuda.empty_cache()
+
+
+def sweep_layout(args):
+    """Runs the stand-alone state_layout_probe (built next to libzc.so): the update's memory
+    pattern over three arrays, over packed arrays of different granules, and with an fp32
+    gradient as a fourth slot.  The probe is a child process; this one never touches the GPU."""
+    import os
+    import subprocess
+    probe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "state_layout_probe")
+    if not os.path.exists(probe):
+        sys.exit(f"tune: {probe} is missing: run `python -m paper_2504_09983_amd.build`")
+    sys.exit(subprocess.call([probe, str(args.elements), args.grads]))
 
 
 def sweep_streams(args):
@@ -386,6 +400,10 @@ def main():
     k.add_argument("--workload", default="llama3_8b", choices=["llama3_8b", "llama3_70b", "mixtral_8x7b"])
     k.add_argument("--reps", type=int, default=0)
     k.set_defaults(fn=sweep_packed)
+    y = sub.add_parser("layout")
+    y.add_argument("--elements", type=int, default=1_003_782_656)
+    y.add_argument("--grads", default="bf16", choices=["bf16", "fp32"])
+    y.set_defaults(fn=sweep_layout)
     sub.add_parser("streams").set_defaults(fn=sweep_streams)
     sub.add_parser("placement").set_defaults(fn=sweep_placement)
     l = sub.add_parser("link")
